@@ -1,0 +1,124 @@
+/*
+ * wq - group-wise int8 quantized Winograd F(m,3) convolution for AMD MI355X (gfx950).
+ *
+ * C ABI of the library built from paper_2412_19867_amd/csrc.  The operation is
+ * the 3x3, stride-1, zero-pad-1 cross-correlation of an NHWC fp32 activation
+ * with OIHW fp32 weights, evaluated as the Winograd pipeline of the paper's
+ * Section "Winograd convolution" (W = G w G^T, X = B^T x B, Y = W . X summed
+ * over input channels, y = A^T Y A) with the Winograd-domain operands
+ * quantized group-wise to int8 as in the second quantized-stage equation of
+ * Section "Learnable Winograd transform scales" (Y ~ s_qW s_qX Q(W/s_qW)
+ * Q(X/s_qX)), the quantizer being the uniform symmetric one of Section
+ * "Related work" with dynamic abs-max scales for activations.
+ *
+ * Conventions
+ *   - n = m+2; taps t = i*n+j (i,j < n); tile grid TH = ceil(H/m), TW = ceil(W/m),
+ *     T = N*TH*TW, tile id (b*TH+th)*TW+tw; groups of `group_size` consecutive
+ *     input channels, groups = Cin/group_size.
+ *   - Every device buffer is owned by the caller.  The library allocates no
+ *     device memory, never synchronises, and enqueues all work on the
+ *     hipStream_t passed as `stream` (NULL = the default stream).
+ *   - `*_dev` pointers are device pointers; everything else is host memory.
+ *   - All functions return a wq_status_t; no exceptions, no global state.
+ *     Distinct plans may be used from distinct threads.  Every argument check
+ *     happens on the host before any kernel is launched.
+ *   - Inputs containing NaN/Inf give unspecified outputs.
+ */
+#ifndef WQ_H
+#define WQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    WQ_OK = 0,
+    WQ_ERR_INVALID_ARG = 1,   /* NULL pointer, non-positive size, Cin % group_size != 0 */
+    WQ_ERR_UNSUPPORTED = 2,   /* m not in {2,4,6}; group_size not in {32,64,128,256,512} */
+    WQ_ERR_BAD_TRANSFORM = 3, /* matrices non-finite or not a valid F(m,3) triple */
+    WQ_ERR_NOT_PREPARED = 4,  /* forward called on a plan that never prepared weights */
+    WQ_ERR_WORKSPACE = 5,     /* a caller buffer is smaller than wq_plan_layout reports */
+    WQ_ERR_DEVICE = 6         /* a kernel launch failed */
+} wq_status_t;
+
+typedef struct wq_plan wq_plan_t; /* opaque host object */
+
+/* Sizes and offsets (bytes) of the library's device-side formats, so that a
+ * caller can allocate the buffers and a test can read the intermediate tensors.
+ *   weight blob : Wq int8 [n*n][Cout_pad][Cin]     at blob_Wq_off
+ *                 sW fp32 [n*n][groups][Cout_pad]  at blob_sW_off
+ *                 bias fp32 [Cout_pad]             at blob_bias_off
+ *   workspace   : Xq int8 [n*n][T_pad][Cin]        at ws_Xq_off
+ *                 sX fp32 [n*n][T_pad][groups]     at ws_sX_off
+ *   debug dump  : P int32 [n*n][T][groups][Cout]   (dense, no padding)
+ * Rows T..T_pad-1 and Cout..Cout_pad-1 hold zeros. */
+typedef struct {
+    int32_t N, H, W, Cin, Cout, m, n, group_size, groups;
+    int32_t TH, TW, T, T_pad, Cout_pad;
+    uint64_t blob_bytes, blob_Wq_off, blob_sW_off, blob_bias_off;
+    uint64_t ws_bytes, ws_Xq_off, ws_sX_off;
+    uint64_t debug_P_bytes;
+} wq_layout_t;
+
+/* The paper's standard F(m,3) matrices (supplementary Section "Standard
+ * Winograd transforms" for m = 4, 6; the same construction with points
+ * 0, 1, -1, infinity for m = 2), row-major fp64, host memory:
+ * BT n*n, G n*3, AT m*n.  Any output pointer may be NULL. */
+wq_status_t wq_standard_transforms(int m, double *BT, double *G, double *AT);
+
+/* Create a plan for one layer shape.  BT (n*n), G (n*3), AT (m*n) are host,
+ * row-major fp32: the transform matrices WITH any learned diagonal scales
+ * already applied (Section "Learnable Winograd transform scales": rows of B^T
+ * and G scaled, columns of A^T scaled by the inverse product).  Pass all three
+ * NULL for the standard matrices.  The matrices are copied.  They must satisfy
+ * sum_i AT[a][i] G[i][k] BT[i][l] = [l == a+k] to 1e-4 relative.
+ * On error *out is set to NULL. */
+wq_status_t wq_plan_create(wq_plan_t **out, int N, int H, int W, int Cin, int Cout,
+                           int m, int group_size,
+                           const float *BT, const float *G, const float *AT);
+
+wq_status_t wq_plan_destroy(wq_plan_t *plan);
+
+wq_status_t wq_plan_layout(const wq_plan_t *plan, wq_layout_t *out);
+
+/* Offline stage (W = G w G^T, then group-wise quantization along Cin):
+ * reads w_dev [Cout][Cin][3][3] fp32 and bias_dev [Cout] fp32 (NULL = zero
+ * bias) and fills weight_blob_dev (blob_bytes, 256-byte aligned). */
+wq_status_t wq_weight_prepare(wq_plan_t *plan, void *stream,
+                              const float *w_dev, const float *bias_dev,
+                              void *weight_blob_dev, size_t blob_bytes);
+
+/* Stage 1 alone (X = B^T x B, dynamic group-wise quantization): reads x_dev
+ * [N][H][W][Cin] fp32 and fills Xq and sX inside workspace_dev. */
+wq_status_t wq_input_transform(const wq_plan_t *plan, void *stream, const float *x_dev,
+                               void *workspace_dev, size_t workspace_bytes);
+
+/* Stages 2+3 alone (int8 contraction with per-group dequantization, then
+ * y = A^T Y A + bias): reads the workspace written by wq_input_transform and
+ * the weight blob, writes y_dev [N][H][W][Cout] fp32. */
+wq_status_t wq_contract_output(const wq_plan_t *plan, void *stream,
+                               const void *workspace_dev, size_t workspace_bytes,
+                               const void *weight_blob_dev, size_t blob_bytes, float *y_dev);
+
+/* The whole forward pass: wq_input_transform followed by wq_contract_output. */
+wq_status_t wq_conv_forward(const wq_plan_t *plan, void *stream, const float *x_dev,
+                            const void *weight_blob_dev, size_t blob_bytes,
+                            void *workspace_dev, size_t workspace_bytes, float *y_dev);
+
+/* Same kernels as wq_conv_forward; additionally stores the exact int32 group
+ * partial sums P[t][tile][group][o] = sum_{c in group} Xq*Wq to P_dev
+ * (debug_P_bytes).  For tests. */
+wq_status_t wq_conv_forward_debug(const wq_plan_t *plan, void *stream, const float *x_dev,
+                                  const void *weight_blob_dev, size_t blob_bytes,
+                                  void *workspace_dev, size_t workspace_bytes, float *y_dev,
+                                  int32_t *P_dev, size_t P_bytes);
+
+const char *wq_status_string(wq_status_t status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* WQ_H */

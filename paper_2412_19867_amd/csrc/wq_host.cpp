@@ -1,0 +1,306 @@
+// Host side of the wq library: plan creation and validation, buffer layouts,
+// the standard transform matrices, and the C-ABI entry points that check
+// their arguments and enqueue the kernels.  Nothing here touches the device
+// except through the launchers in the kernel files.
+#include <cmath>
+#include <cstring>
+#include <new>
+
+#include "wq_internal.h"
+
+namespace {
+
+// Standard F(m,3) matrices (supplementary Section "Standard Winograd
+// transforms"): B^T = diag(S_B) V^{-T}, G = diag(S_G) V, A^T = V^T diag(S_A)
+// for the points 0, 1, -1, 2, -2, (1/2, -1/2,) infinity.
+const double kBT2[16] = {1, 0, -1, 0, 0, 1, 1, 0, 0, -1, 1, 0, 0, 1, 0, -1};
+const double kG2[12] = {1, 0, 0, 0.5, 0.5, 0.5, 0.5, -0.5, 0.5, 0, 0, 1};
+const double kAT2[8] = {1, 1, 1, 0, 0, 1, -1, -1};
+
+const double kBT4[36] = {4, 0,  -5, 0,  1, 0, 0, -4, -4, 1,  1, 0, 0, 4, -4, -1, 1, 0,
+                         0, -2, -1, 2,  1, 0, 0, 2,  -1, -2, 1, 0, 0, 4, 0,  -5, 0, 1};
+const double kG4[18] = {1.0 / 4,  0,        0,       -1.0 / 6, -1.0 / 6,  -1.0 / 6,
+                        -1.0 / 6, 1.0 / 6,  -1.0 / 6, 1.0 / 24, 1.0 / 12, 1.0 / 6,
+                        1.0 / 24, -1.0 / 12, 1.0 / 6, 0,        0,        1};
+const double kAT4[24] = {1, 1, 1, 1, 1, 0, 0, 1, -1, 2, -2, 0, 0, 1, 1, 4, 4, 0, 0, 1, -1, 8, -8, 1};
+
+const double kBT6[64] = {
+    1, 0,    -5.25, 0,     5.25,  0,     -1, 0,   //
+    0, 1,    1,     -4.25, -4.25, 1,     1,  0,   //
+    0, -1,   1,     4.25,  -4.25, -1,    1,  0,   //
+    0, 0.5,  0.25,  -2.5,  -1.25, 2,     1,  0,   //
+    0, -0.5, 0.25,  2.5,   -1.25, -2,    1,  0,   //
+    0, 2,    4,     -2.5,  -5,    0.5,   1,  0,   //
+    0, -2,   4,     2.5,   -5,    -0.5,  1,  0,   //
+    0, -1,   0,     5.25,  0,     -5.25, 0,  1};
+const double kG6[24] = {1,         0,          0,        -2.0 / 9,  -2.0 / 9,  -2.0 / 9,
+                        -2.0 / 9,  2.0 / 9,    -2.0 / 9, 1.0 / 90,  1.0 / 45,  2.0 / 45,
+                        1.0 / 90,  -1.0 / 45,  2.0 / 45, 32.0 / 45, 16.0 / 45, 8.0 / 45,
+                        32.0 / 45, -16.0 / 45, 8.0 / 45, 0,         0,         1};
+const double kAT6[48] = {
+    1, 1, 1,  1,  1,   1,        1,         0,  //
+    0, 1, -1, 2,  -2,  0.5,      -0.5,      0,  //
+    0, 1, 1,  4,  4,   0.25,     0.25,      0,  //
+    0, 1, -1, 8,  -8,  0.125,    -0.125,    0,  //
+    0, 1, 1,  16, 16,  0.0625,   0.0625,    0,  //
+    0, 1, -1, 32, -32, 0.03125,  -0.03125,  1};
+
+bool std_tables(int m, const double **bt, const double **g, const double **at) {
+    switch (m) {
+        case 2: *bt = kBT2; *g = kG2; *at = kAT2; return true;
+        case 4: *bt = kBT4; *g = kG4; *at = kAT4; return true;
+        case 6: *bt = kBT6; *g = kG6; *at = kAT6; return true;
+        default: return false;
+    }
+}
+
+uint64_t align256(uint64_t v) { return (v + 255) & ~uint64_t(255); }
+
+template <int M>
+void detect_patterns(wq_plan *p) {
+    constexpr int n = M + 2;
+    p->sparse_bt = p->sparse_g = p->sparse_at = true;
+    for (int i = 0; i < n; ++i)
+        for (int k = 0; k < n; ++k)
+            if (!wq_pattern<M>::bt(i, k) && p->xf.BT[i * n + k] != 0.0f) p->sparse_bt = false;
+    for (int i = 0; i < n; ++i)
+        for (int k = 0; k < 3; ++k)
+            if (!wq_pattern<M>::g(i, k) && p->xf.G[i * 3 + k] != 0.0f) p->sparse_g = false;
+    for (int a = 0; a < M; ++a)
+        for (int i = 0; i < n; ++i)
+            if (!wq_pattern<M>::at(a, i) && p->xf.AT[a * n + i] != 0.0f) p->sparse_at = false;
+}
+
+// 1-D minimal-filtering identity: the triple computes y[a] = sum_k d[a+k] g[k].
+bool valid_triple(const wq_xf &xf, int m) {
+    const int n = m + 2;
+    for (int i = 0; i < n * n; ++i)
+        if (!std::isfinite(xf.BT[i])) return false;
+    for (int i = 0; i < n * 3; ++i)
+        if (!std::isfinite(xf.G[i])) return false;
+    for (int i = 0; i < m * n; ++i)
+        if (!std::isfinite(xf.AT[i])) return false;
+    for (int a = 0; a < m; ++a)
+        for (int k = 0; k < 3; ++k)
+            for (int l = 0; l < n; ++l) {
+                double s = 0.0, mag = 0.0;
+                for (int i = 0; i < n; ++i) {
+                    double term = (double)xf.AT[a * n + i] * xf.G[i * 3 + k] * xf.BT[i * n + l];
+                    s += term;
+                    mag += std::fabs(term);
+                }
+                const double want = (l == a + k) ? 1.0 : 0.0;
+                if (std::fabs(s - want) > 1e-4 * (mag > 1.0 ? mag : 1.0)) return false;
+            }
+    return true;
+}
+
+wq_status_t check_buffers(const wq_plan *p, const void *blob, size_t blob_bytes, const void *ws,
+                          size_t ws_bytes) {
+    if (!p) return WQ_ERR_INVALID_ARG;
+    if (blob_bytes != (size_t)-1) {
+        if (!blob) return WQ_ERR_INVALID_ARG;
+        if (blob_bytes < p->lay.blob_bytes) return WQ_ERR_WORKSPACE;
+    }
+    if (ws_bytes != (size_t)-1) {
+        if (!ws) return WQ_ERR_INVALID_ARG;
+        if (ws_bytes < p->lay.ws_bytes) return WQ_ERR_WORKSPACE;
+    }
+    return WQ_OK;
+}
+
+struct Blob {
+    const int8_t *Wq;
+    const float *sW;
+    const float *bias;
+};
+Blob blob_of(const wq_plan *p, const void *blob) {
+    const char *b = (const char *)blob;
+    return {(const int8_t *)(b + p->lay.blob_Wq_off), (const float *)(b + p->lay.blob_sW_off),
+            (const float *)(b + p->lay.blob_bias_off)};
+}
+
+}  // namespace
+
+extern "C" {
+
+wq_status_t wq_standard_transforms(int m, double *BT, double *G, double *AT) {
+    const double *bt, *g, *at;
+    if (!std_tables(m, &bt, &g, &at)) return WQ_ERR_UNSUPPORTED;
+    const int n = m + 2;
+    if (BT) std::memcpy(BT, bt, sizeof(double) * n * n);
+    if (G) std::memcpy(G, g, sizeof(double) * n * 3);
+    if (AT) std::memcpy(AT, at, sizeof(double) * m * n);
+    return WQ_OK;
+}
+
+wq_status_t wq_plan_create(wq_plan_t **out, int N, int H, int W, int Cin, int Cout, int m,
+                           int group_size, const float *BT, const float *G, const float *AT) {
+    if (!out) return WQ_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (N <= 0 || H <= 0 || W <= 0 || Cin <= 0 || Cout <= 0 || group_size <= 0)
+        return WQ_ERR_INVALID_ARG;
+    const bool any = BT || G || AT, all = BT && G && AT;
+    if (any && !all) return WQ_ERR_INVALID_ARG;
+    if (m != 2 && m != 4 && m != 6) return WQ_ERR_UNSUPPORTED;
+    if (group_size != 32 && group_size != 64 && group_size != 128 && group_size != 256 &&
+        group_size != 512)
+        return WQ_ERR_UNSUPPORTED;
+    if (Cin % group_size != 0) return WQ_ERR_INVALID_ARG;
+    const int n = m + 2;
+    const long long TH = (H + m - 1) / m, TW = (W + m - 1) / m, T = (long long)N * TH * TW;
+    // 32-bit element indexing inside the kernels
+    if (T + 32 > (1LL << 30) || (T + 32) * Cin > (1LL << 31) - 1 ||
+        (long long)N * H * W * ((Cin > Cout ? Cin : Cout) + 32LL) > (1LL << 31) - 1 ||
+        (long long)(Cout + 32) * Cin > (1LL << 31) - 1)
+        return WQ_ERR_UNSUPPORTED;
+
+    wq_plan *p = new (std::nothrow) wq_plan();
+    if (!p) return WQ_ERR_INVALID_ARG;
+    p->N = N; p->H = H; p->W = W; p->Cin = Cin; p->Cout = Cout; p->m = m; p->n = n;
+    p->g = group_size; p->groups = Cin / group_size;
+    p->TH = (int)TH; p->TW = (int)TW; p->T = (int)T;
+    p->T_pad = (int)((T + 31) / 32 * 32);
+    p->Cout_pad = (Cout + 31) / 32 * 32;
+    p->prepared.store(0);
+    std::memset(&p->xf, 0, sizeof(p->xf));
+    if (all) {
+        std::memcpy(p->xf.BT, BT, sizeof(float) * n * n);
+        std::memcpy(p->xf.G, G, sizeof(float) * n * 3);
+        std::memcpy(p->xf.AT, AT, sizeof(float) * m * n);
+    } else {
+        const double *bt, *g, *at;
+        std_tables(m, &bt, &g, &at);
+        for (int i = 0; i < n * n; ++i) p->xf.BT[i] = (float)bt[i];
+        for (int i = 0; i < n * 3; ++i) p->xf.G[i] = (float)g[i];
+        for (int i = 0; i < m * n; ++i) p->xf.AT[i] = (float)at[i];
+    }
+    if (!valid_triple(p->xf, m)) {
+        delete p;
+        return WQ_ERR_BAD_TRANSFORM;
+    }
+    if (m == 2) detect_patterns<2>(p);
+    else if (m == 4) detect_patterns<4>(p);
+    else detect_patterns<6>(p);
+
+    wq_layout_t &L = p->lay;
+    L.N = N; L.H = H; L.W = W; L.Cin = Cin; L.Cout = Cout; L.m = m; L.n = n;
+    L.group_size = group_size; L.groups = p->groups;
+    L.TH = p->TH; L.TW = p->TW; L.T = p->T; L.T_pad = p->T_pad; L.Cout_pad = p->Cout_pad;
+    const uint64_t n2 = (uint64_t)n * n;
+    L.blob_Wq_off = 0;
+    L.blob_sW_off = align256(n2 * p->Cout_pad * Cin);
+    L.blob_bias_off = L.blob_sW_off + align256(n2 * p->groups * p->Cout_pad * 4);
+    L.blob_bytes = L.blob_bias_off + align256((uint64_t)p->Cout_pad * 4);
+    L.ws_Xq_off = 0;
+    L.ws_sX_off = align256(n2 * p->T_pad * Cin);
+    L.ws_bytes = L.ws_sX_off + align256(n2 * p->T_pad * p->groups * 4);
+    L.debug_P_bytes = n2 * (uint64_t)T * p->groups * Cout * 4;
+    *out = p;
+    return WQ_OK;
+}
+
+wq_status_t wq_plan_destroy(wq_plan_t *plan) {
+    if (!plan) return WQ_ERR_INVALID_ARG;
+    delete plan;
+    return WQ_OK;
+}
+
+wq_status_t wq_plan_layout(const wq_plan_t *plan, wq_layout_t *out) {
+    if (!plan || !out) return WQ_ERR_INVALID_ARG;
+    *out = plan->lay;
+    return WQ_OK;
+}
+
+wq_status_t wq_weight_prepare(wq_plan_t *plan, void *stream, const float *w_dev,
+                              const float *bias_dev, void *weight_blob_dev, size_t blob_bytes) {
+    if (!plan || !w_dev) return WQ_ERR_INVALID_ARG;
+    wq_status_t st = check_buffers(plan, weight_blob_dev, blob_bytes, nullptr, (size_t)-1);
+    if (st != WQ_OK) return st;
+    char *b = (char *)weight_blob_dev;
+    hipError_t e = wq_launch_weight(plan, (hipStream_t)stream, w_dev, bias_dev,
+                                    (int8_t *)(b + plan->lay.blob_Wq_off),
+                                    (float *)(b + plan->lay.blob_sW_off),
+                                    (float *)(b + plan->lay.blob_bias_off));
+    if (e != hipSuccess) return WQ_ERR_DEVICE;
+    plan->prepared.store(1);
+    return WQ_OK;
+}
+
+wq_status_t wq_input_transform(const wq_plan_t *plan, void *stream, const float *x_dev,
+                               void *workspace_dev, size_t workspace_bytes) {
+    if (!plan || !x_dev) return WQ_ERR_INVALID_ARG;
+    wq_status_t st = check_buffers(plan, nullptr, (size_t)-1, workspace_dev, workspace_bytes);
+    if (st != WQ_OK) return st;
+    char *ws = (char *)workspace_dev;
+    hipError_t e = wq_launch_input(plan, (hipStream_t)stream, x_dev,
+                                   (int8_t *)(ws + plan->lay.ws_Xq_off),
+                                   (float *)(ws + plan->lay.ws_sX_off));
+    return e == hipSuccess ? WQ_OK : WQ_ERR_DEVICE;
+}
+
+static wq_status_t contract_impl(const wq_plan_t *plan, void *stream, const void *workspace_dev,
+                                 size_t workspace_bytes, const void *weight_blob_dev,
+                                 size_t blob_bytes, float *y_dev, int32_t *P_dev) {
+    if (!plan || !y_dev) return WQ_ERR_INVALID_ARG;
+    wq_status_t st = check_buffers(plan, weight_blob_dev, blob_bytes, workspace_dev, workspace_bytes);
+    if (st != WQ_OK) return st;
+    if (!plan->prepared.load()) return WQ_ERR_NOT_PREPARED;
+    const char *ws = (const char *)workspace_dev;
+    Blob bl = blob_of(plan, weight_blob_dev);
+    hipError_t e = wq_launch_contract(plan, (hipStream_t)stream,
+                                      (const int8_t *)(ws + plan->lay.ws_Xq_off),
+                                      (const float *)(ws + plan->lay.ws_sX_off), bl.Wq, bl.sW,
+                                      bl.bias, y_dev, P_dev);
+    return e == hipSuccess ? WQ_OK : WQ_ERR_DEVICE;
+}
+
+wq_status_t wq_contract_output(const wq_plan_t *plan, void *stream, const void *workspace_dev,
+                               size_t workspace_bytes, const void *weight_blob_dev,
+                               size_t blob_bytes, float *y_dev) {
+    return contract_impl(plan, stream, workspace_dev, workspace_bytes, weight_blob_dev, blob_bytes,
+                         y_dev, nullptr);
+}
+
+wq_status_t wq_conv_forward(const wq_plan_t *plan, void *stream, const float *x_dev,
+                            const void *weight_blob_dev, size_t blob_bytes, void *workspace_dev,
+                            size_t workspace_bytes, float *y_dev) {
+    if (!plan || !x_dev || !y_dev) return WQ_ERR_INVALID_ARG;
+    wq_status_t st = check_buffers(plan, weight_blob_dev, blob_bytes, workspace_dev, workspace_bytes);
+    if (st != WQ_OK) return st;
+    if (!plan->prepared.load()) return WQ_ERR_NOT_PREPARED;
+    st = wq_input_transform(plan, stream, x_dev, workspace_dev, workspace_bytes);
+    if (st != WQ_OK) return st;
+    return contract_impl(plan, stream, workspace_dev, workspace_bytes, weight_blob_dev, blob_bytes,
+                         y_dev, nullptr);
+}
+
+wq_status_t wq_conv_forward_debug(const wq_plan_t *plan, void *stream, const float *x_dev,
+                                  const void *weight_blob_dev, size_t blob_bytes,
+                                  void *workspace_dev, size_t workspace_bytes, float *y_dev,
+                                  int32_t *P_dev, size_t P_bytes) {
+    if (!plan || !x_dev || !y_dev || !P_dev) return WQ_ERR_INVALID_ARG;
+    wq_status_t st = check_buffers(plan, weight_blob_dev, blob_bytes, workspace_dev, workspace_bytes);
+    if (st != WQ_OK) return st;
+    if (P_bytes < plan->lay.debug_P_bytes) return WQ_ERR_WORKSPACE;
+    if (!plan->prepared.load()) return WQ_ERR_NOT_PREPARED;
+    st = wq_input_transform(plan, stream, x_dev, workspace_dev, workspace_bytes);
+    if (st != WQ_OK) return st;
+    return contract_impl(plan, stream, workspace_dev, workspace_bytes, weight_blob_dev, blob_bytes,
+                         y_dev, P_dev);
+}
+
+const char *wq_status_string(wq_status_t status) {
+    switch (status) {
+        case WQ_OK: return "ok";
+        case WQ_ERR_INVALID_ARG: return "invalid argument";
+        case WQ_ERR_UNSUPPORTED: return "unsupported configuration";
+        case WQ_ERR_BAD_TRANSFORM: return "transform matrices are not a valid F(m,3) triple";
+        case WQ_ERR_NOT_PREPARED: return "weights were never prepared on this plan";
+        case WQ_ERR_WORKSPACE: return "caller buffer too small";
+        case WQ_ERR_DEVICE: return "kernel launch failed";
+    }
+    return "unknown status";
+}
+
+}  // extern "C"

@@ -1,0 +1,236 @@
+"""Thin ctypes binding of libwq.so (include/wq.h).  Argument marshalling only:
+every step of the convolution runs in the library's HIP kernels.  PyTorch is
+used for device memory and streams, nothing else.  There is no fallback: if the
+library is not built, importing a symbol raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libwq.so")
+
+WQ_OK = 0
+STATUS_NAMES = {0: "WQ_OK", 1: "WQ_ERR_INVALID_ARG", 2: "WQ_ERR_UNSUPPORTED",
+                3: "WQ_ERR_BAD_TRANSFORM", 4: "WQ_ERR_NOT_PREPARED", 5: "WQ_ERR_WORKSPACE",
+                6: "WQ_ERR_DEVICE"}
+
+EXPORTS = ["wq_standard_transforms", "wq_plan_create", "wq_plan_destroy", "wq_plan_layout",
+           "wq_weight_prepare", "wq_input_transform", "wq_contract_output", "wq_conv_forward",
+           "wq_conv_forward_debug", "wq_status_string"]
+
+
+class Layout(ctypes.Structure):
+    _fields_ = ([(k, ctypes.c_int32) for k in
+                 ("N", "H", "W", "Cin", "Cout", "m", "n", "group_size", "groups",
+                  "TH", "TW", "T", "T_pad", "Cout_pad")] +
+                [(k, ctypes.c_uint64) for k in
+                 ("blob_bytes", "blob_Wq_off", "blob_sW_off", "blob_bias_off",
+                  "ws_bytes", "ws_Xq_off", "ws_sX_off", "debug_P_bytes")])
+
+
+class WqError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        super().__init__(f"{what}: {STATUS_NAMES.get(status, status)} ({status_string(status)})")
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load libwq.so; raises if it has not been built (no CPU fallback exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: run __graft_entry__.build() "
+                              "(python -m paper_2412_19867_amd.build)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, sz, ip = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
+        L.wq_standard_transforms.argtypes = [ip, vp, vp, vp]
+        L.wq_plan_create.argtypes = [ctypes.POINTER(vp), ip, ip, ip, ip, ip, ip, ip, vp, vp, vp]
+        L.wq_plan_destroy.argtypes = [vp]
+        L.wq_plan_layout.argtypes = [vp, ctypes.POINTER(Layout)]
+        L.wq_weight_prepare.argtypes = [vp, vp, vp, vp, vp, sz]
+        L.wq_input_transform.argtypes = [vp, vp, vp, vp, sz]
+        L.wq_contract_output.argtypes = [vp, vp, vp, sz, vp, sz, vp]
+        L.wq_conv_forward.argtypes = [vp, vp, vp, vp, sz, vp, sz, vp]
+        L.wq_conv_forward_debug.argtypes = [vp, vp, vp, vp, sz, vp, sz, vp, vp, sz]
+        L.wq_status_string.argtypes = [ip]
+        L.wq_status_string.restype = ctypes.c_char_p
+        for name in EXPORTS:
+            if name != "wq_status_string":
+                getattr(L, name).restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().wq_status_string(int(status)).decode()
+
+
+def _check(status: int, what: str):
+    if status != WQ_OK:
+        raise WqError(status, what)
+
+
+def standard_transforms(m: int):
+    """The library's standard (A^T, B^T, G) as float64 arrays."""
+    n = m + 2
+    BT, G, AT = np.empty((n, n)), np.empty((n, 3)), np.empty((m, n))
+    _check(lib().wq_standard_transforms(m, BT.ctypes.data, G.ctypes.data, AT.ctypes.data),
+           "wq_standard_transforms")
+    return AT, BT, G
+
+
+def scaled_transforms(m: int, u_B, u_G):
+    """Apply learned diagonal scales to the standard matrices: rows of B^T by
+    u_B, rows of G by u_G, columns of A^T by 1/(u_B u_G), so that the product of
+    the three diagonal scale matrices stays the identity (Section "Learnable
+    Winograd transform scales").  fp64 in, rounded once to fp32 out."""
+    AT, BT, G = standard_transforms(m)
+    u_B, u_G = np.asarray(u_B, np.float64), np.asarray(u_G, np.float64)
+    if u_B.shape != (m + 2,) or u_G.shape != (m + 2,):
+        raise ValueError("need one scale per row of B^T and of G")
+    if not (np.all(np.isfinite(u_B)) and np.all(np.isfinite(u_G)) and np.all(u_B * u_G != 0)):
+        raise ValueError("scales must be finite and non-zero")
+    return ((AT / (u_B * u_G)[None, :]).astype(np.float32),
+            (BT * u_B[:, None]).astype(np.float32),
+            (G * u_G[:, None]).astype(np.float32))
+
+
+def _stream_handle(stream) -> int:
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return int(s.cuda_stream)
+
+
+def _dev_ptr(t, dtype, what: str, numel: Optional[int] = None) -> int:
+    import torch
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError(f"{what}: expected a device tensor")
+    if t.dtype != dtype or not t.is_contiguous():
+        raise TypeError(f"{what}: expected contiguous {dtype}")
+    if numel is not None and t.numel() != numel:
+        raise ValueError(f"{what}: expected {numel} elements, got {t.numel()}")
+    return t.data_ptr()
+
+
+class Plan:
+    """One layer shape.  Owns only the host-side plan object."""
+
+    def __init__(self, N, H, W, Cin, Cout, m, group_size, AT=None, BT=None, G=None):
+        self._h = ctypes.c_void_p()
+        mats = [None, None, None]
+        if AT is not None or BT is not None or G is not None:
+            mats = [np.ascontiguousarray(a, np.float32) if a is not None else None
+                    for a in (BT, G, AT)]
+            n = m + 2
+            for a, shp in zip(mats, ((n, n), (n, 3), (m, n))):
+                if a is not None and a.shape != shp:
+                    raise ValueError(f"transform matrix shape {a.shape}, expected {shp}")
+        self._mats = mats  # keep alive during the call
+        ptrs = [a.ctypes.data if a is not None else None for a in mats]
+        _check(lib().wq_plan_create(ctypes.byref(self._h), N, H, W, Cin, Cout, m, group_size, *ptrs),
+               "wq_plan_create")
+        self.layout = Layout()
+        _check(lib().wq_plan_layout(self._h, ctypes.byref(self.layout)), "wq_plan_layout")
+
+    def __del__(self):
+        h = getattr(self, "_h", None)
+        if h and _lib is not None:
+            _lib.wq_plan_destroy(h)
+            self._h = None
+
+    # ---- buffers (device memory comes from torch) ----
+    def alloc_blob(self, device="cuda"):
+        import torch
+        return torch.empty(self.layout.blob_bytes, dtype=torch.uint8, device=device)
+
+    def alloc_workspace(self, device="cuda"):
+        import torch
+        return torch.empty(self.layout.ws_bytes, dtype=torch.uint8, device=device)
+
+    def alloc_output(self, device="cuda"):
+        import torch
+        L = self.layout
+        return torch.empty((L.N, L.H, L.W, L.Cout), dtype=torch.float32, device=device)
+
+    def alloc_debug_P(self, device="cuda"):
+        import torch
+        L = self.layout
+        return torch.empty((L.n * L.n, L.T, L.groups, L.Cout), dtype=torch.int32, device=device)
+
+    # ---- views of the library's formats (for tests) ----
+    def blob_views(self, blob):
+        import torch
+        L = self.layout
+        n2 = L.n * L.n
+        Wq = blob[L.blob_Wq_off:L.blob_Wq_off + n2 * L.Cout_pad * L.Cin].view(torch.int8) \
+            .view(n2, L.Cout_pad, L.Cin)
+        sW = blob[L.blob_sW_off:L.blob_sW_off + n2 * L.groups * L.Cout_pad * 4].view(torch.float32) \
+            .view(n2, L.groups, L.Cout_pad)
+        bias = blob[L.blob_bias_off:L.blob_bias_off + L.Cout_pad * 4].view(torch.float32)
+        return Wq, sW, bias
+
+    def workspace_views(self, ws):
+        import torch
+        L = self.layout
+        n2 = L.n * L.n
+        Xq = ws[L.ws_Xq_off:L.ws_Xq_off + n2 * L.T_pad * L.Cin].view(torch.int8) \
+            .view(n2, L.T_pad, L.Cin)
+        sX = ws[L.ws_sX_off:L.ws_sX_off + n2 * L.T_pad * L.groups * 4].view(torch.float32) \
+            .view(n2, L.T_pad, L.groups)
+        return Xq, sX
+
+    # ---- entry points ----
+    def weight_prepare(self, w, bias, blob, stream=None):
+        import torch
+        L = self.layout
+        wp = _dev_ptr(w, torch.float32, "w", L.Cout * L.Cin * 9)
+        bp = None if bias is None else _dev_ptr(bias, torch.float32, "bias", L.Cout)
+        _check(lib().wq_weight_prepare(self._h, _stream_handle(stream), wp, bp,
+                                       _dev_ptr(blob, torch.uint8, "blob"), blob.numel()),
+               "wq_weight_prepare")
+
+    def input_transform(self, x, ws, stream=None):
+        import torch
+        L = self.layout
+        _check(lib().wq_input_transform(self._h, _stream_handle(stream),
+                                        _dev_ptr(x, torch.float32, "x", L.N * L.H * L.W * L.Cin),
+                                        _dev_ptr(ws, torch.uint8, "workspace"), ws.numel()),
+               "wq_input_transform")
+
+    def contract_output(self, ws, blob, y, stream=None):
+        import torch
+        L = self.layout
+        _check(lib().wq_contract_output(self._h, _stream_handle(stream),
+                                        _dev_ptr(ws, torch.uint8, "workspace"), ws.numel(),
+                                        _dev_ptr(blob, torch.uint8, "blob"), blob.numel(),
+                                        _dev_ptr(y, torch.float32, "y", L.N * L.H * L.W * L.Cout)),
+               "wq_contract_output")
+
+    def forward(self, x, blob, ws, y, stream=None):
+        import torch
+        L = self.layout
+        _check(lib().wq_conv_forward(self._h, _stream_handle(stream),
+                                     _dev_ptr(x, torch.float32, "x", L.N * L.H * L.W * L.Cin),
+                                     _dev_ptr(blob, torch.uint8, "blob"), blob.numel(),
+                                     _dev_ptr(ws, torch.uint8, "workspace"), ws.numel(),
+                                     _dev_ptr(y, torch.float32, "y", L.N * L.H * L.W * L.Cout)),
+               "wq_conv_forward")
+
+    def forward_debug(self, x, blob, ws, y, P, stream=None):
+        import torch
+        L = self.layout
+        _check(lib().wq_conv_forward_debug(self._h, _stream_handle(stream),
+                                           _dev_ptr(x, torch.float32, "x", L.N * L.H * L.W * L.Cin),
+                                           _dev_ptr(blob, torch.uint8, "blob"), blob.numel(),
+                                           _dev_ptr(ws, torch.uint8, "workspace"), ws.numel(),
+                                           _dev_ptr(y, torch.float32, "y", L.N * L.H * L.W * L.Cout),
+                                           _dev_ptr(P, torch.int32, "P"), P.numel() * 4),
+               "wq_conv_forward_debug")

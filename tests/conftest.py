@@ -19,3 +19,14 @@ def golden_path(name: str) -> str:
 @pytest.fixture(scope="session")
 def golden():
     return golden_path
+
+
+@pytest.fixture(scope="session")
+def wq():
+    """The ctypes binding; builds libwq.so first only if no built library exists."""
+    from paper_2412_19867_amd import wq as binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2412_19867_amd import build
+        build.build_library()
+    binding.lib()
+    return binding

@@ -1,0 +1,130 @@
+"""Host-side tests of the C-ABI library: they never launch a kernel.
+
+The library loads without a GPU, exports every function include/wq.h declares,
+carries standard matrices equal to the oracle's exact construction, and turns
+every invalid argument into an error code before any device work.
+"""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import cook_toom as ct
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol(wq):
+    header = open(os.path.join(ROOT, "include", "wq.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(wq_[a-z_0-9]+)\s*\(", header))
+    assert declared == set(wq.EXPORTS)
+    L = wq.lib()
+    for name in declared:
+        assert getattr(L, name) is not None
+
+
+@pytest.mark.parametrize("m", [2, 4, 6])
+def test_standard_tables_equal_the_exact_construction(wq, m):
+    AT, BT, G = wq.standard_transforms(m)
+    AT0, BT0, G0 = ct.standard_matrices(m)
+    np.testing.assert_array_equal(AT, AT0)
+    np.testing.assert_array_equal(BT, BT0)
+    np.testing.assert_allclose(G, G0, rtol=2e-16)     # thirds and ninths: one rounding each
+
+
+def test_scaled_transforms_match_the_oracle_parametrisation(wq):
+    rng = np.random.default_rng(0)
+    for m in (4, 6):
+        u_B, u_G = rng.uniform(0.5, 2, m + 2), rng.uniform(0.5, 2, m + 2)
+        AT, BT, G = wq.scaled_transforms(m, u_B, u_G)
+        AT0, BT0, G0 = ct.scaled_matrices(m, u_B, u_G)
+        for a, b in ((AT, AT0), (BT, BT0), (G, G0)):
+            assert a.dtype == np.float32
+            np.testing.assert_allclose(a, b, rtol=1.2e-7)
+    with pytest.raises(ValueError):
+        wq.scaled_transforms(4, np.ones(5), np.ones(6))
+    with pytest.raises(ValueError):
+        wq.scaled_transforms(4, np.zeros(6), np.ones(6))
+
+
+def test_layout_numbers(wq):
+    p = wq.Plan(2, 7, 9, 64, 40, 4, 32)
+    L = p.layout
+    assert (L.n, L.groups, L.TH, L.TW, L.T) == (6, 2, 2, 3, 12)
+    assert L.T_pad % 32 == 0 and L.T_pad >= L.T and L.Cout_pad % 32 == 0 and L.Cout_pad >= 40
+    assert L.blob_sW_off >= 36 * L.Cout_pad * 64 and L.blob_sW_off % 256 == 0
+    assert L.blob_bytes >= L.blob_bias_off + 4 * L.Cout_pad
+    assert L.ws_sX_off >= 36 * L.T_pad * 64 and L.ws_bytes >= L.ws_sX_off + 36 * L.T_pad * 2 * 4
+    assert L.debug_P_bytes == 36 * 12 * 2 * 40 * 4
+
+
+def test_argument_errors_are_host_side(wq):
+    L = wq.lib()
+
+    def create(*a, mats=(None, None, None)):
+        h = ctypes.c_void_p()
+        st = L.wq_plan_create(ctypes.byref(h), *a, *mats)
+        if st == 0:
+            L.wq_plan_destroy(h)
+        else:
+            assert not h.value
+        return st
+
+    assert create(1, 8, 8, 64, 64, 4, 32) == 0
+    assert create(1, 8, 8, 64, 64, 3, 32) == 2          # m
+    assert create(1, 8, 8, 64, 64, 8, 32) == 2
+    assert create(1, 8, 8, 64, 64, 4, 48) == 2          # group size
+    assert create(1, 8, 8, 64, 64, 4, 1024) == 2
+    assert create(1, 8, 8, 96, 64, 4, 64) == 1          # Cin % g
+    assert create(0, 8, 8, 64, 64, 4, 32) == 1
+    assert create(1, 8, -1, 64, 64, 4, 32) == 1
+    assert L.wq_plan_create(None, 1, 8, 8, 64, 64, 4, 32, None, None, None) == 1
+    AT, BT, G = (np.ascontiguousarray(M, np.float32) for M in ct.standard_matrices(4))
+    ptr = lambda a: a.ctypes.data
+    assert create(1, 8, 8, 64, 64, 4, 32, mats=(ptr(BT), ptr(G), ptr(AT))) == 0
+    assert create(1, 8, 8, 64, 64, 4, 32, mats=(ptr(BT), None, ptr(AT))) == 1   # partial set
+    bad = BT.copy(); bad[[1, 2]] = bad[[2, 1]]
+    assert create(1, 8, 8, 64, 64, 4, 32, mats=(ptr(bad), ptr(G), ptr(AT))) == 3
+    bad = G.copy(); bad[3, 1] = np.nan
+    assert create(1, 8, 8, 64, 64, 4, 32, mats=(ptr(BT), ptr(bad), ptr(AT))) == 3
+    bad = AT.copy(); bad[2, 3] *= 1.01
+    assert create(1, 8, 8, 64, 64, 4, 32, mats=(ptr(BT), ptr(G), ptr(bad))) == 3
+    # a diagonal rescaling with S_A S_B S_G = I is accepted
+    ATs, BTs, Gs = wq.scaled_transforms(4, np.linspace(0.5, 2, 6), np.linspace(2, 0.5, 6))
+    assert create(1, 8, 8, 64, 64, 4, 32, mats=(ptr(BTs), ptr(Gs), ptr(ATs))) == 0
+    assert L.wq_plan_destroy(None) == 1
+    assert L.wq_standard_transforms(5, None, None, None) == 2
+
+
+def test_forward_errors_before_any_launch(wq):
+    L = wq.lib()
+    p = wq.Plan(1, 8, 8, 64, 64, 4, 32)
+    lay = p.layout
+    fake = 0x10000  # never dereferenced: every call below must fail on the host
+    big = 1 << 40
+    # never prepared
+    assert L.wq_conv_forward(p._h, None, fake, fake, big, fake, big, fake) == 4
+    assert L.wq_contract_output(p._h, None, fake, big, fake, big, fake) == 4
+    # NULL pointers
+    assert L.wq_conv_forward(p._h, None, None, fake, big, fake, big, fake) == 1
+    assert L.wq_conv_forward(p._h, None, fake, None, big, fake, big, fake) == 1
+    assert L.wq_conv_forward(p._h, None, fake, fake, big, None, big, fake) == 1
+    assert L.wq_conv_forward(p._h, None, fake, fake, big, fake, big, None) == 1
+    assert L.wq_conv_forward(None, None, fake, fake, big, fake, big, fake) == 1
+    assert L.wq_input_transform(p._h, None, None, fake, big) == 1
+    assert L.wq_weight_prepare(p._h, None, None, None, fake, big) == 1
+    # buffers too small
+    assert L.wq_conv_forward(p._h, None, fake, fake, lay.blob_bytes - 1, fake, big, fake) == 5
+    assert L.wq_conv_forward(p._h, None, fake, fake, big, fake, lay.ws_bytes - 1, fake) == 5
+    assert L.wq_input_transform(p._h, None, fake, fake, lay.ws_bytes - 1) == 5
+    assert L.wq_weight_prepare(p._h, None, fake, None, fake, lay.blob_bytes - 1) == 5
+    assert L.wq_conv_forward_debug(p._h, None, fake, fake, big, fake, big, fake, fake,
+                                   lay.debug_P_bytes - 1) == 5
+    assert L.wq_conv_forward_debug(p._h, None, fake, fake, big, fake, big, fake, None, big) == 1
+    for code in range(7):
+        assert wq.status_string(code)
+    with pytest.raises(wq.WqError):
+        wq.Plan(1, 8, 8, 64, 64, 5, 32)

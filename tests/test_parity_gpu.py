@@ -1,0 +1,165 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle.
+
+Bit-exact on the int8 codes, the fp32 scales (they are defined by one rounded
+division) and the int32 group partial sums; fp32 output within 1e-5 of the
+layer's largest output magnitude (normwise-max; a per-element relative bound
+is ill-posed where the Winograd sums cancel).
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from oracle import cook_toom as ct
+from paper_2412_19867_amd import workloads
+
+pytestmark = pytest.mark.gpu
+
+Y_TOL = 1e-5
+
+
+def matrices_for(d, wq):
+    lay = d.layer
+    if d.u_B is not None:
+        lib_mats = wq.scaled_transforms(lay.m, d.u_B, d.u_G)          # what a user would pass
+        ora = tuple(M.astype(np.float32) for M in ct.scaled_matrices(lay.m, d.u_B, d.u_G))
+        for a, b in zip(lib_mats, ora):
+            np.testing.assert_allclose(a, b, rtol=1.2e-7)
+        return ora      # both sides get the oracle-built fp32 matrices as *inputs*
+    return None
+
+
+def run_gpu(wq, d, mats, want_P=True):
+    lay = d.layer
+    kw = {} if mats is None else dict(AT=mats[0], BT=mats[1], G=mats[2])
+    plan = wq.Plan(lay.N, lay.H, lay.W, lay.Cin, lay.Cout, lay.m, lay.group_size, **kw)
+    L = plan.layout
+    blob, ws, y = plan.alloc_blob(), plan.alloc_workspace(), plan.alloc_output()
+    y.fill_(float("nan"))
+    x = torch.from_numpy(d.x).cuda()
+    w = torch.from_numpy(d.w).cuda()
+    b = torch.from_numpy(d.bias).cuda() if d.bias is not None else None
+    plan.weight_prepare(w, b, blob)
+    P = None
+    if want_P:
+        P = plan.alloc_debug_P()
+        plan.forward_debug(x, blob, ws, y, P)
+    else:
+        plan.forward(x, blob, ws, y)
+    torch.cuda.synchronize()
+    Wq, sW, bias = plan.blob_views(blob)
+    Xq, sX = plan.workspace_views(ws)
+    out = dict(Wq=Wq[:, :L.Cout].cpu().numpy(), sW=sW[:, :, :L.Cout].cpu().numpy(),
+               Xq=Xq[:, :L.T].cpu().numpy(), sX=sX[:, :L.T].cpu().numpy(),
+               y=y.cpu().numpy(), P=None if P is None else P.cpu().numpy(),
+               pad_ok=bool((Wq[:, L.Cout:] == 0).all() and (sW[:, :, L.Cout:] == 0).all()
+                           and (Xq[:, L.T:] == 0).all() and (sX[:, L.T:] == 0).all()
+                           and (bias[L.Cout:] == 0).all()))
+    return out
+
+
+def check(wq, d, want_P=True):
+    lay = d.layer
+    mats = matrices_for(d, wq)
+    if mats is None:
+        AT, BT, G = ct.standard_matrices(lay.m)
+    else:
+        AT, BT, G = mats
+    ref = oracle.qwino_pipeline(d.x, d.w, d.bias, AT, BT, G, lay.m, lay.group_size, want_P=want_P)
+    got = run_gpu(wq, d, mats, want_P=want_P)
+    assert got["pad_ok"]
+    for key in ("Wq", "Xq"):
+        bad = np.count_nonzero(got[key] != ref[key])
+        assert bad == 0, f"{lay.name}: {key} differs in {bad} of {ref[key].size} codes"
+    for key in ("sW", "sX"):
+        assert np.array_equal(got[key].view(np.uint32), ref[key].view(np.uint32)), f"{lay.name}: {key}"
+    if want_P:
+        assert np.array_equal(got["P"], ref["P"]), f"{lay.name}: int32 partial sums"
+    assert np.isfinite(got["y"]).all(), f"{lay.name}: output has unwritten or non-finite entries"
+    err = np.abs(got["y"].astype(np.float64) - ref["y64"]).max()
+    scale = np.abs(ref["y64"]).max()
+    assert err <= Y_TOL * scale, f"{lay.name}: max|err| {err:.3e} > {Y_TOL * scale:.3e}"
+    return err / scale
+
+
+SMALL = [
+    # seed N  H   W  Cin Cout m  g   scaled
+    (1, 1, 8, 8, 32, 16, 4, 32, False),
+    (2, 2, 7, 10, 64, 48, 4, 32, False),      # ragged tiles, Cout padded
+    (3, 1, 13, 6, 64, 33, 6, 32, True),       # odd Cout, learned-scale style matrices
+    (4, 3, 9, 9, 128, 64, 4, 64, True),
+    (5, 1, 5, 5, 32, 32, 2, 32, False),
+    (6, 2, 12, 12, 256, 32, 6, 128, False),
+    (7, 1, 6, 20, 512, 16, 4, 256, True),
+    (8, 1, 4, 4, 512, 32, 2, 512, False),
+    (9, 5, 11, 11, 96, 80, 6, 32, False),     # > 32 tiles: several tile blocks and a tail
+    (10, 1, 1, 1, 32, 1, 4, 32, False),       # a single pixel
+]
+
+
+@pytest.mark.parametrize("case", SMALL, ids=lambda c: "s%d_%dx%dx%d_%d-%d_F%d_g%d" % c[:8])
+def test_small_layers(wq, case):
+    seed, N, H, W, Cin, Cout, m, g, scaled = case
+    d = workloads.small_layer(seed, N, H, W, Cin, Cout, m, g, row_scales=scaled)
+    check(wq, d)
+
+
+def test_no_bias_and_repeatability(wq):
+    d = workloads.small_layer(21, 2, 9, 7, 64, 32, 4, 32)
+    d.bias = None
+    check(wq, d)
+    a = run_gpu(wq, d, None)
+    b = run_gpu(wq, d, None)
+    assert np.array_equal(a["y"], b["y"]) and np.array_equal(a["Xq"], b["Xq"])
+
+
+def test_dense_matrices_take_the_generic_kernels(wq):
+    """A valid F(4,3) triple from six finite points has none of the standard
+    zeros, so the kernels that skip them cannot be selected."""
+    pts = [(0, 1), (1, 1), (-1, 1), (2, 1), (-2, 1), (3, 1)]
+    AT, BT, G = ct.cook_toom(pts, [1] * 6, [1] * 6, [1] * 6, 4)
+    assert ct.identity_defect(AT, BT, G) == 0
+    mats = tuple(ct.to_f64(M).astype(np.float32) for M in (AT, BT, G))
+    assert np.count_nonzero(mats[1]) > 24
+    d = workloads.small_layer(31, 1, 9, 10, 64, 32, 4, 32)
+    lay = d.layer
+    ref = oracle.qwino_pipeline(d.x, d.w, d.bias, *mats, lay.m, lay.group_size, want_P=True)
+    got = run_gpu(wq, d, mats)
+    for key in ("Wq", "Xq", "P"):
+        assert np.array_equal(got[key], ref[key]), key
+    for key in ("sW", "sX"):
+        assert np.array_equal(got[key].view(np.uint32), ref[key].view(np.uint32)), key
+    err = np.abs(got["y"].astype(np.float64) - ref["y64"]).max()
+    assert err <= Y_TOL * np.abs(ref["y64"]).max()
+
+
+def test_degenerate_groups(wq):
+    """All-zero input, a zero group, a sub-normal group and a group at the
+    smallest quantized magnitude."""
+    d = workloads.small_layer(41, 1, 8, 8, 64, 32, 4, 32)
+    d.x[...] = 0
+    check(wq, d)
+    d = workloads.small_layer(42, 1, 8, 8, 64, 32, 4, 32)
+    d.x[..., :32] = 0                       # one whole group zero everywhere
+    d.w[:, 32:] = 0
+    check(wq, d)
+    d = workloads.small_layer(43, 1, 8, 8, 64, 32, 4, 32)
+    d.x[..., :32] *= np.float32(1e-41)      # sub-normal activations in group 0
+    d.x[..., 32:] *= np.float32(3e-38)
+    check(wq, d)
+
+
+def test_config1_full(wq):
+    check(wq, workloads.make_layer_data(workloads.CONFIGS[1][0]))
+
+
+FULL = [(c, i) for c in (2, 3, 4, 5) for i in range(len(workloads.CONFIGS[c]))]
+
+
+@pytest.mark.parametrize("cfg,idx", FULL, ids=lambda v: str(v))
+def test_config_layers_full_size(wq, cfg, idx):
+    lay = workloads.CONFIGS[cfg][idx]
+    d = workloads.make_layer_data(lay)
+    n2 = lay.n ** 2
+    p_bytes = n2 * lay.tiles * (lay.Cin // lay.group_size) * lay.Cout * 4
+    check(wq, d, want_P=p_bytes <= 300 << 20)

@@ -62,40 +62,52 @@ __global__ __launch_bounds__(64 * (M + 2)) void k_contract_output(
         const int8_t *xp = Xq + ((size_t)t * T_pad + tau0 + l16) * Cin + q * KB;
         const float *swp = sW + (size_t)t * groups * Cout_pad + o0 + 4 * q;
         const float *sxp = sX + ((size_t)t * T_pad + tau0 + l16) * groups;
-        float4 Mv = make_float4(0.f, 0.f, 0.f, 0.f);
-        for (int gi = 0; gi < groups; ++gi) {
-            v4i acc = {0, 0, 0, 0};
-            if constexpr (K64) {
-                for (int kk = 0; kk < g; kk += 64) {
-                    const v4i a = *reinterpret_cast<const v4i *>(wp + gi * g + kk);
-                    const v4i b = *reinterpret_cast<const v4i *>(xp + gi * g + kk);
-                    acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b, acc, 0, 0, 0);
+        // fp32 partial sums over chunks of 4 groups, chunk totals added in fp64:
+        // keeps the rounding of long reductions (many groups) out of the
+        // cancelling sums of the output transform.
+        double Mt0 = 0.0, Mt1 = 0.0, Mt2 = 0.0, Mt3 = 0.0;
+        for (int g0 = 0; g0 < groups; g0 += 4) {
+            const int g1 = min(g0 + 4, groups);
+            float4 Mc = make_float4(0.f, 0.f, 0.f, 0.f);
+            for (int gi = g0; gi < g1; ++gi) {
+                v4i acc = {0, 0, 0, 0};
+                if constexpr (K64) {
+                    for (int kk = 0; kk < g; kk += 64) {
+                        const v4i a = *reinterpret_cast<const v4i *>(wp + gi * g + kk);
+                        const v4i b = *reinterpret_cast<const v4i *>(xp + gi * g + kk);
+                        acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b, acc, 0, 0, 0);
+                    }
+                } else {
+                    for (int kk = 0; kk < g; kk += 32) {
+                        const long a = *reinterpret_cast<const long *>(wp + gi * g + kk);
+                        const long b = *reinterpret_cast<const long *>(xp + gi * g + kk);
+                        acc = __builtin_amdgcn_mfma_i32_16x16x32_i8(a, b, acc, 0, 0, 0);
+                    }
                 }
-            } else {
-                for (int kk = 0; kk < g; kk += 32) {
-                    const long a = *reinterpret_cast<const long *>(wp + gi * g + kk);
-                    const long b = *reinterpret_cast<const long *>(xp + gi * g + kk);
-                    acc = __builtin_amdgcn_mfma_i32_16x16x32_i8(a, b, acc, 0, 0, 0);
-                }
-            }
-            const float4 sw = *reinterpret_cast<const float4 *>(swp + (size_t)gi * Cout_pad);
-            const float sx = sxp[gi];
-            Mv.x = __builtin_fmaf((float)acc[0], sw.x * sx, Mv.x);
-            Mv.y = __builtin_fmaf((float)acc[1], sw.y * sx, Mv.y);
-            Mv.z = __builtin_fmaf((float)acc[2], sw.z * sx, Mv.z);
-            Mv.w = __builtin_fmaf((float)acc[3], sw.w * sx, Mv.w);
-            if constexpr (DUMP) {
-                const int tau = tau0 + l16;
-                if (tau < T) {
+                const float4 sw = *reinterpret_cast<const float4 *>(swp + (size_t)gi * Cout_pad);
+                const float sx = sxp[gi];
+                Mc.x = __builtin_fmaf((float)acc[0], sw.x * sx, Mc.x);
+                Mc.y = __builtin_fmaf((float)acc[1], sw.y * sx, Mc.y);
+                Mc.z = __builtin_fmaf((float)acc[2], sw.z * sx, Mc.z);
+                Mc.w = __builtin_fmaf((float)acc[3], sw.w * sx, Mc.w);
+                if constexpr (DUMP) {
+                    const int tau = tau0 + l16;
+                    if (tau < T) {
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        const int o = o0 + 4 * q + r;
-                        if (o < Cout)
-                            P[(((size_t)t * T + tau) * groups + gi) * Cout + o] = acc[r];
+                        for (int r = 0; r < 4; ++r) {
+                            const int o = o0 + 4 * q + r;
+                            if (o < Cout)
+                                P[(((size_t)t * T + tau) * groups + gi) * Cout + o] = acc[r];
+                        }
                     }
                 }
             }
+            Mt0 += (double)Mc.x;
+            Mt1 += (double)Mc.y;
+            Mt2 += (double)Mc.z;
+            Mt3 += (double)Mc.w;
         }
+        const float4 Mv = make_float4((float)Mt0, (float)Mt1, (float)Mt2, (float)Mt3);
 #pragma unroll
         for (int b = 0; b < M; ++b)
             if (!ATSP || Pat::at(b, j)) {

@@ -1,0 +1,221 @@
+#!/usr/bin/env python3
+"""Benchmark of the group-wise int8 quantized Winograd convolution on one MI355X.
+
+A step is one forward pass (input transform + quantization, int8 contraction
+with per-group dequantization, output transform + bias) over every layer of
+the workload, inputs and prepared weights resident in HBM.  The weight
+transform is the method's offline stage: it runs once before the timed region
+and is timed separately (reported under "offline_stage", and as a second
+whole-job figure "with_offline_stage" that re-runs it every step).
+
+Prints ONE JSON line.  `value` = direct-equivalent int8 TOPS of the layer set
+(2*N*H*W*Cin*Cout*9 per layer / measured time).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+INT8_PEAK_TOPS = 5000.0        # MI355X published dense int8 MFMA rate
+
+
+def k1_bytes(lay):
+    n2, G = lay.n ** 2, lay.Cin // lay.group_size
+    return 4 * lay.N * lay.H * lay.W * lay.Cin + n2 * lay.tiles * (lay.Cin + 4 * G)
+
+
+def k2_bytes(lay):
+    n2, G = lay.n ** 2, lay.Cin // lay.group_size
+    return (n2 * lay.tiles * (lay.Cin + 4 * G) + n2 * lay.Cout * (lay.Cin + 4 * G)
+            + 4 * lay.N * lay.H * lay.W * lay.Cout)
+
+
+def k3_bytes(lay):
+    n2, G = lay.n ** 2, lay.Cin // lay.group_size
+    return 36 * lay.Cin * lay.Cout + n2 * lay.Cout * (lay.Cin + 4 * G)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=2, help="layer set 1..5 (2 = the headline one)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
+                 "(the path shards without communication over tiles or output channels; "
+                 "see DESIGN.md)")
+
+    import numpy as np
+    import torch
+    from paper_2412_19867_amd import wq, workloads
+
+    wq.lib()   # fails loudly when the HIP library is missing; there is no fallback
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    stream = torch.cuda.current_stream()
+
+    layers = workloads.CONFIGS[args.config]
+    items = []      # one entry per conv launched in a step (a layer with repeat=r gives r chained convs)
+    for lay in layers:
+        d = workloads.make_layer_data(lay)
+        kw = {}
+        if d.u_B is not None:
+            AT, BT, G = wq.scaled_transforms(lay.m, d.u_B, d.u_G)
+            kw = dict(AT=AT, BT=BT, G=G)
+        plan = wq.Plan(lay.N, lay.H, lay.W, lay.Cin, lay.Cout, lay.m, lay.group_size, **kw)
+        x = torch.from_numpy(d.x).cuda()
+        w, b = torch.from_numpy(d.w).cuda(), torch.from_numpy(d.bias).cuda()
+        for r in range(lay.repeat):
+            # conv r of a stack reads conv r-1's output (Cin == Cout) and has its own weight blob
+            it = dict(lay=lay, plan=plan, x=x, w=w, b=b, blob=plan.alloc_blob(),
+                      ws=plan.alloc_workspace(), y=plan.alloc_output(), data=d, first=(r == 0))
+            plan.weight_prepare(w, b, it["blob"])
+            items.append(it)
+            x = it["y"]
+    torch.cuda.synchronize()
+
+    def step(with_offline=False):
+        for it in items:
+            if with_offline:
+                it["plan"].weight_prepare(it["w"], it["b"], it["blob"])
+            it["plan"].forward(it["x"], it["blob"], it["ws"], it["y"])
+
+    def timed(fn, steps, warmup):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps
+
+    sec = timed(step, args.steps, args.warmup)
+    n_convs = len(items)
+    direct_ops = sum(it['lay'].direct_ops for it in items)
+    value = direct_ops / sec / 1e12
+
+    sec_off = timed(lambda: step(True), max(10, args.steps // 4), 3)
+
+    # ---- per-kernel durations: HIP events on the launch stream, same launch order ----
+    reps = max(20, min(args.steps, 100))
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2 * len(items) + 1)] for _ in range(reps)]
+    for _ in range(3):
+        step()
+    torch.cuda.synchronize()
+    for r in range(reps):
+        ev[r][0].record(stream)
+        for k, it in enumerate(items):
+            it["plan"].input_transform(it["x"], it["ws"])
+            ev[r][2 * k + 1].record(stream)
+            it["plan"].contract_output(it["ws"], it["blob"], it["y"])
+            ev[r][2 * k + 2].record(stream)
+    torch.cuda.synchronize()
+    k1_us = [float(np.mean([ev[r][2 * k].elapsed_time(ev[r][2 * k + 1]) for r in range(reps)])) * 1e3
+             for k in range(len(items))]
+    k2_us = [float(np.mean([ev[r][2 * k + 1].elapsed_time(ev[r][2 * k + 2]) for r in range(reps)])) * 1e3
+             for k in range(len(items))]
+    # offline stage per layer
+    k3_us = []
+    for it in items:
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        it["plan"].weight_prepare(it["w"], it["b"], it["blob"])
+        e0.record(stream)
+        for _ in range(10):
+            it["plan"].weight_prepare(it["w"], it["b"], it["blob"])
+        e1.record(stream)
+        torch.cuda.synchronize()
+        k3_us.append(e0.elapsed_time(e1) * 1e3 / 10)
+
+    per_layer = []
+    for k, it in enumerate(items):
+        lay = it["lay"]
+        t_us = k1_us[k] + k2_us[k]
+        per_layer.append(dict(
+            layer=lay.name, us=round(t_us, 2), k1_us=round(k1_us[k], 2), k2_us=round(k2_us[k], 2),
+            direct_equiv_tops=round(lay.direct_ops / t_us / 1e6, 1),
+            k1_hbm_frac=round(k1_bytes(lay) / (k1_us[k] * 1e-6) / 1e9 / HBM_PEAK_GBS, 3),
+            k2_hbm_frac=round(k2_bytes(lay) / (k2_us[k] * 1e-6) / 1e9 / HBM_PEAK_GBS, 3),
+            k2_mfma_frac=round(2 * lay.n ** 2 * lay.tiles * lay.Cin * lay.Cout
+                               / (k2_us[k] * 1e-6) / 1e12 / INT8_PEAK_TOPS, 4),
+            k3_us=round(k3_us[k], 2),
+            k3_hbm_frac=round(k3_bytes(lay) / (k3_us[k] * 1e-6) / 1e9 / HBM_PEAK_GBS, 3)))
+
+    # dominant kernel of the step = the contraction+output-transform kernel or the input transform
+    tot_k1, tot_k2 = sum(k1_us), sum(k2_us)
+    if tot_k2 >= tot_k1:
+        dom, dom_bytes, dom_us = "k_contract_output", sum(k2_bytes(it["lay"]) for it in items), tot_k2
+    else:
+        dom, dom_bytes, dom_us = "k_input_transform", sum(k1_bytes(it["lay"]) for it in items), tot_k1
+    achieved = dom_bytes / (dom_us * 1e-6) / 1e9
+    roofline = dict(bound="hbm", kernel=dom, achieved=round(achieved, 1), peak=HBM_PEAK_GBS,
+                    unit="GB/s", frac=round(achieved / HBM_PEAK_GBS, 4), traffic=None,
+                    algorithmic_bytes_per_step=dom_bytes, avg_launch_us=round(dom_us / len(items), 2),
+                    launches_per_step=len(items))
+
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        import oracle
+        from oracle import cook_toom as ct
+        prepared = []
+        for it in items:
+            if not it["first"]:
+                continue
+            lay, d = it["lay"], it["data"]
+            if d.u_B is not None:
+                AT, BT, G = (M.astype(np.float32) for M in ct.scaled_matrices(lay.m, d.u_B, d.u_G))
+            else:
+                AT, BT, G = (M.astype(np.float32) for M in ct.standard_matrices(lay.m))
+            Wq, sW = oracle.weight_transform_quant(d.w, G, lay.m, lay.group_size)
+            prepared.append((lay, d, AT, BT, Wq, sW))
+
+        def cpu_pass():
+            for lay, d, AT, BT, Wq, sW in prepared:
+                Xq, sX = oracle.input_transform_quant(d.x, BT, lay.m, lay.group_size)
+                M = oracle.contract(Xq, sX, Wq, sW, lay.group_size)
+                oracle.output_transform(M, AT, d.bias, lay.N, lay.H, lay.W, lay.m)
+
+        cpu_pass()
+        t0 = time.perf_counter()
+        passes = 0
+        while passes < 3 or (time.perf_counter() - t0 < 10 and passes < 50):
+            cpu_pass()
+            passes += 1
+        cpu_sec = (time.perf_counter() - t0) / passes
+        cpu_ops = sum(l.direct_ops for l in layers)
+        cpu_baseline = dict(value=round(cpu_ops / cpu_sec / 1e12, 5), unit="TOPS",
+                            cores=oracle.threads(), kind="oracle",
+                            sample=f"{passes} forward passes over the full layer set (one conv per "
+                                   f"layer, weights prepared beforehand), {cpu_sec:.2f} s per pass",
+                            ms_per_pass=round(cpu_sec * 1e3, 1))
+
+    out = dict(
+        metric="direct-equivalent int8 TOPS of the group-wise quantized Winograd conv layer set "
+               "(2*N*H*W*Cin*Cout*9 per layer / time); per-layer us in 'layers'",
+        value=round(value, 2), unit="TOPS", n_gpus=1, steps=args.steps, warmup=args.warmup,
+        ms_per_step=round(sec * 1e3, 4), us_per_layer=round(sec * 1e6 / n_convs, 2),
+        higher_is_better=True, scaling="weak", vs_baseline=None, dtype="int8",
+        data="synthetic",
+        config=dict(workload=f"configs[{args.config - 1}]: " + "; ".join(l.name for l in layers),
+                    winograd=f"F({layers[0].m},3)", group_size=layers[0].group_size,
+                    batch=layers[0].N, convs_per_step=n_convs),
+        roofline=roofline, cpu_baseline=cpu_baseline,
+        with_offline_stage=dict(value=round(direct_ops / sec_off / 1e12, 2), unit="TOPS",
+                                ms_per_step=round(sec_off * 1e3, 4)),
+        layers=per_layer)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -37,7 +37,8 @@ extern "C" {
 typedef enum {
     WQ_OK = 0,
     WQ_ERR_INVALID_ARG = 1,   /* NULL pointer, non-positive size, Cin % group_size != 0 */
-    WQ_ERR_UNSUPPORTED = 2,   /* m not in {2,4,6}; group_size not in {32,64,128,256,512} */
+    WQ_ERR_UNSUPPORTED = 2,   /* m not in {2,4,6}; group_size not in {32,64,128,256,512};
+                                 a tensor of 2 GiB or more (input: more than 1 GiB) */
     WQ_ERR_BAD_TRANSFORM = 3, /* matrices non-finite or not a valid F(m,3) triple */
     WQ_ERR_NOT_PREPARED = 4,  /* forward called on a plan that never prepared weights */
     WQ_ERR_WORKSPACE = 5,     /* a caller buffer is smaller than wq_plan_layout reports */
@@ -48,16 +49,21 @@ typedef struct wq_plan wq_plan_t; /* opaque host object */
 
 /* Sizes and offsets (bytes) of the library's device-side formats, so that a
  * caller can allocate the buffers and a test can read the intermediate tensors.
- *   weight blob : Wq int8 [n*n][Cout_pad][Cin]     at blob_Wq_off
+ *   weight blob : Wq int8, blocked            at blob_Wq_off
  *                 sW fp32 [n*n][groups][Cout_pad]  at blob_sW_off
  *                 bias fp32 [Cout_pad]             at blob_bias_off
- *   workspace   : Xq int8 [n*n][T_pad][Cin]        at ws_Xq_off
- *                 sX fp32 [n*n][T_pad][groups]     at ws_sX_off
+ *   workspace   : Xq int8, blocked            at ws_Xq_off
+ *                 sX fp32 [n*n][T_pad/16][groups][16]  at ws_sX_off  (last index = tile % 16)
  *   debug dump  : P int32 [n*n][T][groups][Cout]   (dense, no padding)
+ * Blocked int8 layout (R = T_pad for Xq, Cout_pad for Wq; the MFMA operand order):
+ *   [n*n][R/16][Cin/kstep][4][16][kstep/4]
+ *   element (tap, row, c) sits at block (tap, row/16, c/kstep), then
+ *   q = (c % kstep) / (kstep/4), then row % 16, then c % (kstep/4);
+ *   kstep = 32 for group_size 32, else 64.
  * Rows T..T_pad-1 and Cout..Cout_pad-1 hold zeros. */
 typedef struct {
     int32_t N, H, W, Cin, Cout, m, n, group_size, groups;
-    int32_t TH, TW, T, T_pad, Cout_pad;
+    int32_t TH, TW, T, T_pad, Cout_pad, kstep;
     uint64_t blob_bytes, blob_Wq_off, blob_sW_off, blob_bias_off;
     uint64_t ws_bytes, ws_Xq_off, ws_sX_off;
     uint64_t debug_P_bytes;

@@ -17,7 +17,8 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(ROOT, "_build")
 LIB = os.path.join(HERE, "libwq.so")
-SOURCES = ["wq_host.cpp", "wq_transform.hip", "wq_contract.hip"]
+SOURCES = ["wq_host.cpp", "wq_transform.hip", "wq_contract.hip", "wq_contract_m2.hip",
+           "wq_contract_m4.hip", "wq_contract_m6.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -25,12 +26,12 @@ FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-ffp-contract=o
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 
 
-def build_library(verbose: bool = False, extra_flags=()) -> str:
-    os.makedirs(BUILD, exist_ok=True)
+def build_library(verbose: bool = False, extra_flags=(), lib_out: str = LIB, build_dir: str = BUILD) -> str:
+    os.makedirs(build_dir, exist_ok=True)
     procs = []
     objs = []
     for src in SOURCES:
-        obj = os.path.join(BUILD, os.path.splitext(src)[0] + ".o")
+        obj = os.path.join(build_dir, os.path.splitext(src)[0] + ".o")
         objs.append(obj)
         cmd = [HIPCC, "-x", "hip", *FLAGS, *extra_flags, "-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
@@ -49,9 +50,9 @@ def build_library(verbose: bool = False, extra_flags=()) -> str:
             print(text)
     if failed:
         raise RuntimeError("hipcc failed")
-    cmd = [HIPCC, "-shared", "-fPIC", "--offload-arch=gfx950", *objs, "-o", LIB]
+    cmd = [HIPCC, "-shared", "-fPIC", "--offload-arch=gfx950", *objs, "-o", lib_out]
     subprocess.run(cmd, check=True)
-    return LIB
+    return lib_out
 
 
 if __name__ == "__main__":

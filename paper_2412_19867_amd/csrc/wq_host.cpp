@@ -149,11 +149,16 @@ wq_status_t wq_plan_create(wq_plan_t **out, int N, int H, int W, int Cin, int Co
     if (Cin % group_size != 0) return WQ_ERR_INVALID_ARG;
     const int n = m + 2;
     const long long TH = (H + m - 1) / m, TW = (W + m - 1) / m, T = (long long)N * TH * TW;
-    // 32-bit element indexing inside the kernels
-    if (T + 32 > (1LL << 30) || (T + 32) * Cin > (1LL << 31) - 1 ||
-        (long long)N * H * W * ((Cin > Cout ? Cin : Cout) + 32LL) > (1LL << 31) - 1 ||
-        (long long)(Cout + 32) * Cin > (1LL << 31) - 1)
-        return WQ_ERR_UNSUPPORTED;
+    // 32-bit byte offsets inside the kernels (buffer addressing): every tensor below 2 GiB,
+    // the input below 1 GiB (its out-of-image offsets are pushed past the end by adding 2^30)
+    {
+        const long long n2 = (long long)n * n, Tp = (T + 31) / 32 * 32, Cp = (Cout + 31) / 32 * 32;
+        const long long lim = (1LL << 31) - 1;
+        if ((long long)N * H * W * Cin * 4 > (1LL << 30) || (long long)N * H * W * Cout * 4 > lim ||
+            n2 * Tp * Cin > lim || n2 * Cp * Cin > lim || n2 * Tp * (Cin / group_size) * 4 > lim ||
+            n2 * Cp * (Cin / group_size) * 4 > lim)
+            return WQ_ERR_UNSUPPORTED;
+    }
 
     wq_plan *p = new (std::nothrow) wq_plan();
     if (!p) return WQ_ERR_INVALID_ARG;
@@ -162,6 +167,7 @@ wq_status_t wq_plan_create(wq_plan_t **out, int N, int H, int W, int Cin, int Co
     p->TH = (int)TH; p->TW = (int)TW; p->T = (int)T;
     p->T_pad = (int)((T + 31) / 32 * 32);
     p->Cout_pad = (Cout + 31) / 32 * 32;
+    p->kstep = group_size == 32 ? 32 : 64;
     p->prepared.store(0);
     std::memset(&p->xf, 0, sizeof(p->xf));
     if (all) {
@@ -187,6 +193,7 @@ wq_status_t wq_plan_create(wq_plan_t **out, int N, int H, int W, int Cin, int Co
     L.N = N; L.H = H; L.W = W; L.Cin = Cin; L.Cout = Cout; L.m = m; L.n = n;
     L.group_size = group_size; L.groups = p->groups;
     L.TH = p->TH; L.TW = p->TW; L.T = p->T; L.T_pad = p->T_pad; L.Cout_pad = p->Cout_pad;
+    L.kstep = p->kstep;
     const uint64_t n2 = (uint64_t)n * n;
     L.blob_Wq_off = 0;
     L.blob_sW_off = align256(n2 * p->Cout_pad * Cin);

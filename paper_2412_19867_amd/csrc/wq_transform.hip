@@ -3,9 +3,11 @@
 //
 // Both kernels share one skeleton.  A workgroup of 256 threads is 16 DPP rows
 // of 16 lanes; a row owns one "unit" = (tile or output channel, 32 consecutive
-// input channels), a lane owns 2 of those channels.  Units are numbered so
-// that unit u starts at byte 32*u of every tap plane of the int8 output, which
-// makes all stores of a workgroup contiguous.
+// input channels), a lane owns 2 of those channels.  With k = group_size/32,
+// a workgroup holds 16/k consecutive tiles (output channels) times the k
+// units of ONE quantization group, so every group is reduced inside one
+// workgroup and the int8 codes of a workgroup land in whole cache lines of
+// the blocked operand layout (see include/wq.h).
 //   phase A  each lane transforms its two channels with fused-multiply-add
 //            chains (left factor first, inner index ascending, from +0) and
 //            reduces |value| over its row with four DPP steps per tap;
@@ -14,6 +16,10 @@
 //            stores s; r goes through LDS;
 //   phase C  every lane quantizes its values as rint(v*r) (rounded product,
 //            then round-half-even via the 1.5*2^23 add) and stores two codes.
+// The input kernel additionally splits the n tap rows over blockIdx.y (two
+// rows per workgroup): B^T d only has to be formed for those rows, so the
+// split costs nothing but re-reading the tile through L1, and it quarters the
+// length of the per-wave instruction stream, which is what bounds this kernel.
 // The arithmetic order is part of the library's contract: the int8 codes and
 // scales are reproducible bit for bit from the definition in include/wq.h.
 #include <float.h>
@@ -22,17 +28,22 @@
 
 namespace {
 
+typedef int v2i __attribute__((ext_vector_type(2)));
+constexpr int kBufFlags = 0x00020000;   // raw buffer, 32-bit elements (gfx9 family)
+constexpr unsigned kInvalid = 1u << 30;  // added to an offset to push it past the buffer end
+
 template <int CTRL>
-__device__ __forceinline__ uint32_t dpp_mov(uint32_t v) {
-    return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, CTRL, 0xf, 0xf, false);
+__device__ __forceinline__ uint32_t dpp_max(uint32_t v) {
+    // bound_ctrl with a zero fill lets the compiler fold the move into v_max_u32_dpp
+    return max(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xf, 0xf, true));
 }
 
 // max over the 16 lanes of a DPP row, result in every lane
 __device__ __forceinline__ uint32_t row_max16(uint32_t v) {
-    v = max(v, dpp_mov<0xB1>(v));   // quad_perm [1,0,3,2]
-    v = max(v, dpp_mov<0x4E>(v));   // quad_perm [2,3,0,1]
-    v = max(v, dpp_mov<0x141>(v));  // row_half_mirror
-    v = max(v, dpp_mov<0x140>(v));  // row_mirror
+    v = dpp_max<0xB1>(v);   // quad_perm [1,0,3,2]
+    v = dpp_max<0x4E>(v);   // quad_perm [2,3,0,1]
+    v = dpp_max<0x141>(v);  // row_half_mirror
+    v = dpp_max<0x140>(v);  // row_mirror
     return v;
 }
 
@@ -45,115 +56,179 @@ __device__ __forceinline__ uint32_t quant_code(float v, float r) {
     return __float_as_uint(z) & 0xffu;
 }
 
-// Phases B and C.  `vals` are the lane's transformed values [tap][2],
-// `amax_s`/`r_s` LDS tables [n2][16].  log2k = log2(rows per group).
-// scale_index(t, first_unit_of_group) gives the element index of the scale.
-template <int N2, typename ScaleIndex>
-__device__ __forceinline__ void quantize_and_store(const float2 (&vals)[N2], uint32_t (*amax_s)[16],
-                                                   float (*r_s)[16], int log2k, long unit_base,
-                                                   long n_units, long plane_bytes, int8_t *codes,
-                                                   float *scales, ScaleIndex scale_index) {
-    const int tid = threadIdx.x, row = tid >> 4, l16 = tid & 15;
-    const int k = 1 << log2k, ng_log2 = 4 - log2k, ng = 1 << ng_log2;
+// Byte offset of a lane's two codes inside one 16-row block of the operand
+// layout [K-step][q][row][KB]: `chunk` = 32-channel chunk index of the unit,
+// `row16` = row inside the block.
+__device__ __forceinline__ unsigned blocked_offset(int chunk, int row16, int l16, int kstep_log2) {
+    if (kstep_log2 == 5)   // K-step 32: q = l16/4, 8 bytes per (q,row)
+        return ((unsigned)chunk * 64u + (unsigned)(l16 >> 2) * 16u + (unsigned)row16) * 8u +
+               (unsigned)((2 * l16) & 7);
+    // K-step 64: two chunks per K-step, q = (chunk&1)*2 + l16/8, 16 bytes per (q,row)
+    return ((unsigned)(chunk >> 1) * 64u + (unsigned)((chunk & 1) * 2 + (l16 >> 3)) * 16u +
+            (unsigned)row16) * 16u + (unsigned)((2 * l16) & 15);
+}
+
+// Phases B and C for NT consecutive taps starting at tap t0.
+//   amax_s/r_s   LDS [NT][16]
+//   log2k        log2(units per group); the workgroup holds 16>>log2k rows-of-groups
+//   code_rsrc    buffer over the int8 tensor; lane_off = the lane's byte offset inside a tap plane
+//   scale index  scale_base + t*scale_plane + item (item = row-of-group index inside the workgroup)
+template <int NT>
+__device__ __forceinline__ void quantize_and_store(const float2 (&vals)[NT], uint32_t (*amax_s)[16],
+                                                   float (*r_s)[16], int log2k, int t0,
+                                                   __amdgpu_buffer_rsrc_t code_rsrc, unsigned lane_off,
+                                                   unsigned plane_bytes, bool lane_ok,
+                                                   float *__restrict__ scales, long scale_base,
+                                                   long scale_plane, int items_ok) {
+    const int tid = threadIdx.x, row = tid >> 4;
+    const int k = 1 << log2k, ni_log2 = 4 - log2k, ni = 1 << ni_log2;   // ni items per tap
     __syncthreads();
-    for (int it = tid; it < N2 * ng; it += 256) {
-        const int t = it >> ng_log2, gi = it & (ng - 1);
+    for (int it = tid; it < NT * ni; it += 256) {
+        const int tl = it >> ni_log2, item = it & (ni - 1);
         uint32_t a = 0;
-        for (int q = 0; q < k; ++q) a = max(a, amax_s[t][gi * k + q]);
+        for (int q = 0; q < k; ++q) a = max(a, amax_s[tl][item * k + q]);
         const float af = __uint_as_float(a);
         float s = 0.0f, r = 0.0f;
         if (af >= 127.0f * FLT_MIN) {
             s = af / 127.0f;   // correctly rounded (hipcc default for fp32 division)
             r = 127.0f / af;
         }
-        r_s[t][gi] = r;
-        const long u0 = unit_base + (long)gi * k;
-        if (u0 < n_units) scales[scale_index(t, u0)] = s;
+        r_s[tl][item] = r;
+        if (item < items_ok) scales[scale_base + (long)(t0 + tl) * scale_plane + item] = s;
     }
     __syncthreads();
-    const long u = unit_base + row;
-    if (u < n_units) {
-        int8_t *dst = codes + u * 32 + l16 * 2;
-        const int gi = row >> log2k;
+    if (lane_ok) {
+        const int item = row >> log2k;
 #pragma unroll
-        for (int t = 0; t < N2; ++t) {
-            const float r = r_s[t][gi];
-            const uint32_t c = quant_code(vals[t].x, r) | (quant_code(vals[t].y, r) << 8);
-            *reinterpret_cast<uint16_t *>(dst + (long)t * plane_bytes) = (uint16_t)c;
+        for (int tl = 0; tl < NT; ++tl) {
+            const float r = r_s[tl][item];
+            const uint32_t c = quant_code(vals[tl].x, r) | (quant_code(vals[tl].y, r) << 8);
+            __builtin_amdgcn_raw_buffer_store_b16((short)c, code_rsrc, lane_off,
+                                                  (unsigned)(t0 + tl) * plane_bytes, 0);
         }
     }
 }
 
 // ---------------------------------------------------------------- stage 1
+constexpr int TR = 2;   // tap rows per workgroup of the input kernel
+
+template <int M, int I0, bool SPARSE>
+__device__ __forceinline__ void input_body(const wq_xf &xf, const float *__restrict__ x,
+                                           int8_t *__restrict__ Xq, float *__restrict__ sX, int H,
+                                           int W, int Cin, int TH, int TW, int T, int T_pad,
+                                           int log2k, int kstep_log2, unsigned x_bytes,
+                                           uint32_t (*amax_s)[16], float (*r_s)[16]) {
+    constexpr int n = M + 2, NT = TR * n;
+    using Pat = wq_pattern<M>;
+    const int tid = threadIdx.x, row = tid >> 4, l16 = tid & 15;
+    const int k = 1 << log2k;
+    const int CC = Cin >> 5, groups = CC >> log2k;
+    // blockIdx.x -> (16-tile block rb, sub-block of 16/k tiles, group)
+    const int rb = blockIdx.x / CC, rem = blockIdx.x % CC;
+    const int sub = rem / groups, gam = rem % groups;
+    const int row16 = sub * (16 >> log2k) + (row >> log2k);      // tile inside the 16-tile block
+    const int chunk = gam * k + (row & (k - 1));
+    const int tau = rb * 16 + row16;
+    const bool tile_ok = tau < T;
+    const int tw = tau % TW, th = (tau / TW) % TH, b = tau / (TW * TH);
+    const int h0 = th * M - 1, w0 = tw * M - 1;
+
+    const __amdgpu_buffer_rsrc_t rx =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(x), 0, (int)x_bytes, kBufFlags);
+    // byte offsets of the tile's rows and columns; anything outside the image
+    // (or a padding tile) is pushed past the end of the buffer and loads as zero
+    unsigned roff[n], coff[n];
+#pragma unroll
+    for (int e = 0; e < n; ++e) {
+        const int hh = h0 + e, ww = w0 + e;
+        roff[e] = (tile_ok && hh >= 0 && hh < H) ? (unsigned)((b * H + hh) * W) * (unsigned)Cin * 4u
+                                                 : kInvalid;
+        coff[e] = (ww >= 0 && ww < W) ? (unsigned)(ww * Cin + chunk * 32 + l16 * 2) * 4u : kInvalid;
+    }
+
+    // first product, rows I0..I0+TR-1 of Tm = B^T d, one input column at a time
+    float2 Tm[TR][n];
+#pragma unroll
+    for (int j = 0; j < n; ++j) {
+        float2 d[n];
+#pragma unroll
+        for (int kk = 0; kk < n; ++kk) {
+            const v2i v = __builtin_amdgcn_raw_buffer_load_b64(rx, roff[kk] + coff[j], 0, 0);
+            d[kk] = make_float2(__int_as_float(v.x), __int_as_float(v.y));
+        }
+#pragma unroll
+        for (int r = 0; r < TR; ++r) {
+            const int i = I0 + r;
+            float ax = 0.0f, ay = 0.0f;
+#pragma unroll
+            for (int kk = 0; kk < n; ++kk)
+                if (!SPARSE || Pat::bt(i, kk)) {
+                    ax = __builtin_fmaf(xf.BT[i * n + kk], d[kk].x, ax);
+                    ay = __builtin_fmaf(xf.BT[i * n + kk], d[kk].y, ay);
+                }
+            Tm[r][j] = make_float2(ax, ay);
+        }
+    }
+    // second product X = Tm B, abs-max of each tap over the row's 32 channels
+    float2 X[NT];
+#pragma unroll
+    for (int r = 0; r < TR; ++r) {
+        uint32_t am[n];
+#pragma unroll
+        for (int j = 0; j < n; ++j) {
+            float ax = 0.0f, ay = 0.0f;
+#pragma unroll
+            for (int kk = 0; kk < n; ++kk)
+                if (!SPARSE || Pat::bt(j, kk)) {
+                    ax = __builtin_fmaf(Tm[r][kk].x, xf.BT[j * n + kk], ax);
+                    ay = __builtin_fmaf(Tm[r][kk].y, xf.BT[j * n + kk], ay);
+                }
+            X[r * n + j] = make_float2(ax, ay);
+            am[j] = row_max16(max(abs_bits(ax), abs_bits(ay)));
+        }
+        if (l16 == 0) {
+#pragma unroll
+            for (int j = 0; j < n; ++j) amax_s[r * n + j][row] = am[j];
+        }
+    }
+    const int RB = T_pad >> 4;
+    const __amdgpu_buffer_rsrc_t rq = __builtin_amdgcn_make_buffer_rsrc(
+        Xq, 0, (int)((unsigned)(n * n) * (unsigned)T_pad * (unsigned)Cin), kBufFlags);
+    const unsigned lane_off =
+        (unsigned)rb * 16u * (unsigned)Cin + blocked_offset(chunk, row16, l16, kstep_log2);
+    // sX [t][rb][group][16]: this workgroup owns 16/k consecutive entries per tap
+    const long scale_base = ((long)rb * groups + gam) * 16 + sub * (16 >> log2k);
+    quantize_and_store<NT>(X, amax_s, r_s, log2k, I0 * n, rq, lane_off,
+                           (unsigned)T_pad * (unsigned)Cin, true, sX, scale_base,
+                           (long)RB * groups * 16, 16);
+}
+
 template <int M, bool SPARSE>
 __global__ __launch_bounds__(256) void k_input_transform(wq_xf xf, const float *__restrict__ x,
                                                          int8_t *__restrict__ Xq,
                                                          float *__restrict__ sX, int H, int W,
                                                          int Cin, int TH, int TW, int T, int T_pad,
-                                                         int log2k) {
-    constexpr int n = M + 2, n2 = n * n;
-    using Pat = wq_pattern<M>;
-    __shared__ uint32_t amax_s[n2][16];
-    __shared__ float r_s[n2][16];
-    const int tid = threadIdx.x, row = tid >> 4, l16 = tid & 15;
-    const int CC = Cin >> 5;
-    const long n_units = (long)T_pad * CC;
-    const long unit_base = (long)blockIdx.x * 16;
-    const long u = unit_base + row;
-    const bool unit_ok = u < n_units;
-    const int tau = unit_ok ? (int)(u / CC) : 0;
-    const int chunk = unit_ok ? (int)(u % CC) : 0;
-    const bool tile_ok = unit_ok && tau < T;
-    const int tw = tau % TW, th = (tau / TW) % TH, b = tau / (TW * TH);
-    const int h0 = th * M - 1, w0 = tw * M - 1;
-    const float *xb = x + (size_t)b * H * W * Cin + chunk * 32 + l16 * 2;
-
-    // first product Tm = B^T d, one input column at a time
-    float2 Tm[n][n];
-#pragma unroll
-    for (int j = 0; j < n; ++j) {
-        float2 d[n];
-        const int ww = w0 + j;
-#pragma unroll
-        for (int k = 0; k < n; ++k) {
-            const int hh = h0 + k;
-            const bool ok = tile_ok && hh >= 0 && hh < H && ww >= 0 && ww < W;
-            d[k] = ok ? *reinterpret_cast<const float2 *>(xb + ((size_t)hh * W + ww) * Cin)
-                      : make_float2(0.0f, 0.0f);
-        }
-#pragma unroll
-        for (int i = 0; i < n; ++i) {
-            float ax = 0.0f, ay = 0.0f;
-#pragma unroll
-            for (int k = 0; k < n; ++k)
-                if (!SPARSE || Pat::bt(i, k)) {
-                    ax = __builtin_fmaf(xf.BT[i * n + k], d[k].x, ax);
-                    ay = __builtin_fmaf(xf.BT[i * n + k], d[k].y, ay);
-                }
-            Tm[i][j] = make_float2(ax, ay);
+                                                         int log2k, int kstep_log2,
+                                                         unsigned x_bytes) {
+    constexpr int n = M + 2;
+    __shared__ uint32_t amax_s[TR * n][16];
+    __shared__ float r_s[TR * n][16];
+#define WQ_BODY(I0)                                                                            \
+    input_body<M, (I0), SPARSE>(xf, x, Xq, sX, H, W, Cin, TH, TW, T, T_pad, log2k, kstep_log2, \
+                                x_bytes, amax_s, r_s)
+    const int split = blockIdx.y;   // uniform: tap rows 2*split, 2*split+1
+    if (split == 0) {
+        WQ_BODY(0);
+    } else if (split == 1) {
+        WQ_BODY(2);
+    } else if constexpr (n >= 6) {
+        if (split == 2) {
+            WQ_BODY(4);
+        } else if constexpr (n >= 8) {
+            WQ_BODY(6);
         }
     }
-    // second product X = Tm B, abs-max of each tap over the row's 32 channels
-    float2 X[n2];
-#pragma unroll
-    for (int i = 0; i < n; ++i)
-#pragma unroll
-        for (int j = 0; j < n; ++j) {
-            float ax = 0.0f, ay = 0.0f;
-#pragma unroll
-            for (int k = 0; k < n; ++k)
-                if (!SPARSE || Pat::bt(j, k)) {
-                    ax = __builtin_fmaf(Tm[i][k].x, xf.BT[j * n + k], ax);
-                    ay = __builtin_fmaf(Tm[i][k].y, xf.BT[j * n + k], ay);
-                }
-            X[i * n + j] = make_float2(ax, ay);
-            const uint32_t a = row_max16(max(abs_bits(ax), abs_bits(ay)));
-            if (l16 == 0) amax_s[i * n + j][row] = a;
-        }
-    const int groups = CC >> log2k;
-    const long sx_plane = (long)T_pad * groups;
-    quantize_and_store<n2>(X, amax_s, r_s, log2k, unit_base, n_units, (long)T_pad * Cin, Xq, sX,
-                           [=](int t, long u0) { return (long)t * sx_plane + (u0 >> log2k); });
+#undef WQ_BODY
 }
 
 // ----------------------------------------------------------- offline stage
@@ -161,20 +236,20 @@ template <int M, bool SPARSE>
 __global__ __launch_bounds__(256) void k_weight_transform(wq_xf xf, const float *__restrict__ w,
                                                           int8_t *__restrict__ Wq,
                                                           float *__restrict__ sW, int Cin, int Cout,
-                                                          int Cout_pad, int log2k) {
+                                                          int Cout_pad, int log2k, int kstep_log2) {
     constexpr int n = M + 2, n2 = n * n;
     using Pat = wq_pattern<M>;
     __shared__ uint32_t amax_s[n2][16];
     __shared__ float r_s[n2][16];
     const int tid = threadIdx.x, row = tid >> 4, l16 = tid & 15;
-    const int CC = Cin >> 5;
-    const long n_units = (long)Cout_pad * CC;
-    const long unit_base = (long)blockIdx.x * 16;
-    const long u = unit_base + row;
-    const bool unit_ok = u < n_units;
-    const int o = unit_ok ? (int)(u / CC) : 0;
-    const int chunk = unit_ok ? (int)(u % CC) : 0;
-    const bool ok = unit_ok && o < Cout;
+    const int k = 1 << log2k;
+    const int CC = Cin >> 5, groups = CC >> log2k;
+    const int rb = blockIdx.x / CC, rem = blockIdx.x % CC;
+    const int sub = rem / groups, gam = rem % groups;
+    const int row16 = sub * (16 >> log2k) + (row >> log2k);
+    const int chunk = gam * k + (row & (k - 1));
+    const int o = rb * 16 + row16;
+    const bool ok = o < Cout;
 
     // the lane's two 3x3 filters are 18 consecutive floats
     float f[18];
@@ -195,35 +270,43 @@ __global__ __launch_bounds__(256) void k_weight_transform(wq_xf xf, const float 
             for (int bcol = 0; bcol < 3; ++bcol) {
                 float ax = 0.0f, ay = 0.0f;
 #pragma unroll
-                for (int k = 0; k < 3; ++k)
-                    if (!SPARSE || Pat::g(i, k)) {
-                        ax = __builtin_fmaf(xf.G[i * 3 + k], f[k * 3 + bcol], ax);
-                        ay = __builtin_fmaf(xf.G[i * 3 + k], f[9 + k * 3 + bcol], ay);
+                for (int kk = 0; kk < 3; ++kk)
+                    if (!SPARSE || Pat::g(i, kk)) {
+                        ax = __builtin_fmaf(xf.G[i * 3 + kk], f[kk * 3 + bcol], ax);
+                        ay = __builtin_fmaf(xf.G[i * 3 + kk], f[9 + kk * 3 + bcol], ay);
                     }
                 U[i][bcol] = make_float2(ax, ay);
             }
 #pragma unroll
-        for (int i = 0; i < n; ++i)
+        for (int i = 0; i < n; ++i) {
+            uint32_t am[n];
 #pragma unroll
             for (int j = 0; j < n; ++j) {
                 float ax = 0.0f, ay = 0.0f;
 #pragma unroll
-                for (int k = 0; k < 3; ++k)
-                    if (!SPARSE || Pat::g(j, k)) {
-                        ax = __builtin_fmaf(U[i][k].x, xf.G[j * 3 + k], ax);
-                        ay = __builtin_fmaf(U[i][k].y, xf.G[j * 3 + k], ay);
+                for (int kk = 0; kk < 3; ++kk)
+                    if (!SPARSE || Pat::g(j, kk)) {
+                        ax = __builtin_fmaf(U[i][kk].x, xf.G[j * 3 + kk], ax);
+                        ay = __builtin_fmaf(U[i][kk].y, xf.G[j * 3 + kk], ay);
                     }
                 X[i * n + j] = make_float2(ax, ay);
-                const uint32_t a = row_max16(max(abs_bits(ax), abs_bits(ay)));
-                if (l16 == 0) amax_s[i * n + j][row] = a;
+                am[j] = row_max16(max(abs_bits(ax), abs_bits(ay)));
             }
+            if (l16 == 0) {
+#pragma unroll
+                for (int j = 0; j < n; ++j) amax_s[i * n + j][row] = am[j];
+            }
+        }
     }
-    const int groups = CC >> log2k;
-    quantize_and_store<n2>(X, amax_s, r_s, log2k, unit_base, n_units, (long)Cout_pad * Cin, Wq, sW,
-                           [=](int t, long u0) {
-                               const long oo = u0 / CC, gam = (u0 % CC) >> log2k;
-                               return ((long)t * groups + gam) * Cout_pad + oo;
-                           });
+    const __amdgpu_buffer_rsrc_t rq = __builtin_amdgcn_make_buffer_rsrc(
+        Wq, 0, (int)((unsigned)n2 * (unsigned)Cout_pad * (unsigned)Cin), kBufFlags);
+    const unsigned lane_off =
+        (unsigned)rb * 16u * (unsigned)Cin + blocked_offset(chunk, row16, l16, kstep_log2);
+    // sW [t][group][Cout_pad]: this workgroup owns 16/k consecutive output channels
+    const long scale_base = (long)gam * Cout_pad + rb * 16 + sub * (16 >> log2k);
+    quantize_and_store<n2>(X, amax_s, r_s, log2k, 0, rq, lane_off,
+                           (unsigned)Cout_pad * (unsigned)Cin, true, sW, scale_base,
+                           (long)groups * Cout_pad, 16);
 }
 
 __global__ void k_copy_bias(const float *__restrict__ bias, float *__restrict__ out, int Cout,
@@ -240,29 +323,28 @@ int ilog2(int v) {
 
 template <int M>
 hipError_t launch_input_m(const wq_plan *p, hipStream_t s, const float *x, int8_t *Xq, float *sX) {
-    const long units = (long)p->T_pad * (p->Cin / 32);
-    const dim3 grid((unsigned)((units + 15) / 16)), block(256);
-    const int log2k = ilog2(p->g / 32);
+    const dim3 grid((unsigned)((p->T_pad / 16) * (p->Cin / 32)), (M + 2) / TR), block(256);
+    const int log2k = ilog2(p->g / 32), kstep_log2 = p->kstep == 32 ? 5 : 6;
+    const unsigned x_bytes = (unsigned)((size_t)p->N * p->H * p->W * p->Cin * 4);
     if (p->sparse_bt)
         hipLaunchKernelGGL((k_input_transform<M, true>), grid, block, 0, s, p->xf, x, Xq, sX, p->H,
-                           p->W, p->Cin, p->TH, p->TW, p->T, p->T_pad, log2k);
+                           p->W, p->Cin, p->TH, p->TW, p->T, p->T_pad, log2k, kstep_log2, x_bytes);
     else
         hipLaunchKernelGGL((k_input_transform<M, false>), grid, block, 0, s, p->xf, x, Xq, sX, p->H,
-                           p->W, p->Cin, p->TH, p->TW, p->T, p->T_pad, log2k);
+                           p->W, p->Cin, p->TH, p->TW, p->T, p->T_pad, log2k, kstep_log2, x_bytes);
     return hipGetLastError();
 }
 
 template <int M>
 hipError_t launch_weight_m(const wq_plan *p, hipStream_t s, const float *w, int8_t *Wq, float *sW) {
-    const long units = (long)p->Cout_pad * (p->Cin / 32);
-    const dim3 grid((unsigned)((units + 15) / 16)), block(256);
-    const int log2k = ilog2(p->g / 32);
+    const dim3 grid((unsigned)((p->Cout_pad / 16) * (p->Cin / 32))), block(256);
+    const int log2k = ilog2(p->g / 32), kstep_log2 = p->kstep == 32 ? 5 : 6;
     if (p->sparse_g)
         hipLaunchKernelGGL((k_weight_transform<M, true>), grid, block, 0, s, p->xf, w, Wq, sW,
-                           p->Cin, p->Cout, p->Cout_pad, log2k);
+                           p->Cin, p->Cout, p->Cout_pad, log2k, kstep_log2);
     else
         hipLaunchKernelGGL((k_weight_transform<M, false>), grid, block, 0, s, p->xf, w, Wq, sW,
-                           p->Cin, p->Cout, p->Cout_pad, log2k);
+                           p->Cin, p->Cout, p->Cout_pad, log2k, kstep_log2);
     return hipGetLastError();
 }
 

@@ -27,7 +27,7 @@ EXPORTS = ["wq_standard_transforms", "wq_plan_create", "wq_plan_destroy", "wq_pl
 class Layout(ctypes.Structure):
     _fields_ = ([(k, ctypes.c_int32) for k in
                  ("N", "H", "W", "Cin", "Cout", "m", "n", "group_size", "groups",
-                  "TH", "TW", "T", "T_pad", "Cout_pad")] +
+                  "TH", "TW", "T", "T_pad", "Cout_pad", "kstep")] +
                 [(k, ctypes.c_uint64) for k in
                  ("blob_bytes", "blob_Wq_off", "blob_sW_off", "blob_bias_off",
                   "ws_bytes", "ws_Xq_off", "ws_sX_off", "debug_P_bytes")])
@@ -165,26 +165,35 @@ class Plan:
         L = self.layout
         return torch.empty((L.n * L.n, L.T, L.groups, L.Cout), dtype=torch.int32, device=device)
 
-    # ---- views of the library's formats (for tests) ----
+    # ---- views of the library's formats (for tests): pure index permutations ----
+    def _unblock(self, flat, rows):
+        """[n*n][rows/16][Cin/kstep][4][16][kstep/4] -> [n*n][rows][Cin]"""
+        L = self.layout
+        n2, ks = L.n * L.n, L.kstep
+        v = flat.view(n2, rows // 16, L.Cin // ks, 4, 16, ks // 4)
+        return v.permute(0, 1, 4, 2, 3, 5).reshape(n2, rows, L.Cin)
+
     def blob_views(self, blob):
+        """(Wq [n*n][Cout_pad][Cin] int8, sW [n*n][groups][Cout_pad] fp32, bias [Cout_pad])"""
         import torch
         L = self.layout
         n2 = L.n * L.n
-        Wq = blob[L.blob_Wq_off:L.blob_Wq_off + n2 * L.Cout_pad * L.Cin].view(torch.int8) \
-            .view(n2, L.Cout_pad, L.Cin)
+        Wq = self._unblock(blob[L.blob_Wq_off:L.blob_Wq_off + n2 * L.Cout_pad * L.Cin]
+                           .view(torch.int8), L.Cout_pad)
         sW = blob[L.blob_sW_off:L.blob_sW_off + n2 * L.groups * L.Cout_pad * 4].view(torch.float32) \
             .view(n2, L.groups, L.Cout_pad)
         bias = blob[L.blob_bias_off:L.blob_bias_off + L.Cout_pad * 4].view(torch.float32)
         return Wq, sW, bias
 
     def workspace_views(self, ws):
+        """(Xq [n*n][T_pad][Cin] int8, sX [n*n][T_pad][groups] fp32)"""
         import torch
         L = self.layout
         n2 = L.n * L.n
-        Xq = ws[L.ws_Xq_off:L.ws_Xq_off + n2 * L.T_pad * L.Cin].view(torch.int8) \
-            .view(n2, L.T_pad, L.Cin)
+        Xq = self._unblock(ws[L.ws_Xq_off:L.ws_Xq_off + n2 * L.T_pad * L.Cin].view(torch.int8),
+                           L.T_pad)
         sX = ws[L.ws_sX_off:L.ws_sX_off + n2 * L.T_pad * L.groups * 4].view(torch.float32) \
-            .view(n2, L.T_pad, L.groups)
+            .view(n2, L.T_pad // 16, L.groups, 16).permute(0, 1, 3, 2).reshape(n2, L.T_pad, L.groups)
         return Xq, sX
 
     # ---- entry points ----

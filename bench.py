@@ -3,10 +3,13 @@
 
 A step is one forward pass (input transform + quantization, int8 contraction
 with per-group dequantization, output transform + bias) over every layer of
-the workload, inputs and prepared weights resident in HBM.  The weight
-transform is the method's offline stage: it runs once before the timed region
-and is timed separately (reported under "offline_stage", and as a second
-whole-job figure "with_offline_stage" that re-runs it every step).
+the workload, inputs and prepared weights resident in HBM.  The step's kernel
+launches are captured once into a HIP graph (the layers are a few microseconds
+each, so host launch cost would otherwise dominate) and the timed region
+replays that graph.  The weight transform is the method's offline stage: it
+runs once before the timed region and is timed separately (per layer in
+"layers", and as a second whole-job figure "with_offline_stage" that re-runs
+it inside every step).
 
 Prints ONE JSON line.  `value` = direct-equivalent int8 TOPS of the layer set
 (2*N*H*W*Cin*Cout*9 per layer / measured time).
@@ -41,6 +44,20 @@ def k2_bytes(lay):
 def k3_bytes(lay):
     n2, G = lay.n ** 2, lay.Cin // lay.group_size
     return 36 * lay.Cin * lay.Cout + n2 * lay.Cout * (lay.Cin + 4 * G)
+
+
+def measured_traffic(kernel, cfg):
+    """HBM bytes per step of the dominant kernel as measured with rocprofv3 --pmc
+    (FETCH_SIZE + WRITE_SIZE, calibrated against a copy kernel); read from the
+    committed summary, None when there is none for this kernel and layer set."""
+    path = os.path.join(ROOT, "profiles", f"{kernel}_cfg{cfg}_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_step:"):
+                return int(float(line.split(":")[1]))
+    except OSError:
+        pass
+    return None
 
 
 def main():
@@ -91,52 +108,71 @@ def main():
                 it["plan"].weight_prepare(it["w"], it["b"], it["blob"])
             it["plan"].forward(it["x"], it["blob"], it["ws"], it["y"])
 
-    def timed(fn, steps, warmup):
-        for _ in range(warmup):
-            fn()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(steps):
-            fn()
-        torch.cuda.synchronize()
-        return (time.perf_counter() - t0) / steps
+    side = torch.cuda.Stream()
 
-    sec = timed(step, args.steps, args.warmup)
+    def capture(fn):
+        """Record fn's launches on a side stream into a HIP graph."""
+        with torch.cuda.stream(side):
+            fn()
+            side.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                fn()
+        torch.cuda.synchronize()
+        return g
+
+    def timed_replays(g, steps, warmup):
+        with torch.cuda.stream(side):
+            for _ in range(warmup):
+                g.replay()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                g.replay()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) / steps
+
+    g_step = capture(step)
+    sec = timed_replays(g_step, args.steps, args.warmup)
     n_convs = len(items)
     direct_ops = sum(it['lay'].direct_ops for it in items)
     value = direct_ops / sec / 1e12
 
-    sec_off = timed(lambda: step(True), max(10, args.steps // 4), 3)
-
-    # ---- per-kernel durations: HIP events on the launch stream, same launch order ----
-    reps = max(20, min(args.steps, 100))
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2 * len(items) + 1)] for _ in range(reps)]
-    for _ in range(3):
+    # the same step launched eagerly from Python (host-launch bound for these small layers)
+    for _ in range(5):
         step()
     torch.cuda.synchronize()
-    for r in range(reps):
-        ev[r][0].record(stream)
-        for k, it in enumerate(items):
-            it["plan"].input_transform(it["x"], it["ws"])
-            ev[r][2 * k + 1].record(stream)
-            it["plan"].contract_output(it["ws"], it["blob"], it["y"])
-            ev[r][2 * k + 2].record(stream)
+    t0 = time.perf_counter()
+    for _ in range(50):
+        step()
     torch.cuda.synchronize()
-    k1_us = [float(np.mean([ev[r][2 * k].elapsed_time(ev[r][2 * k + 1]) for r in range(reps)])) * 1e3
-             for k in range(len(items))]
-    k2_us = [float(np.mean([ev[r][2 * k + 1].elapsed_time(ev[r][2 * k + 2]) for r in range(reps)])) * 1e3
-             for k in range(len(items))]
-    # offline stage per layer
-    k3_us = []
-    for it in items:
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        it["plan"].weight_prepare(it["w"], it["b"], it["blob"])
-        e0.record(stream)
-        for _ in range(10):
-            it["plan"].weight_prepare(it["w"], it["b"], it["blob"])
-        e1.record(stream)
-        torch.cuda.synchronize()
-        k3_us.append(e0.elapsed_time(e1) * 1e3 / 10)
+    sec_eager = (time.perf_counter() - t0) / 50
+
+    g_off = capture(lambda: step(True))
+    sec_off = timed_replays(g_off, max(10, args.steps // 4), 3)
+
+    # ---- per-kernel durations: HIP events on the replay stream around a graph that
+    # launches ONE kernel REPS times back to back (so the figure is device time, not
+    # host launch cost) ----
+    REPS = 20
+
+    def kernel_us(fn):
+        g = capture(lambda: [fn() for _ in range(REPS)])
+        with torch.cuda.stream(side):
+            g.replay()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(side)
+            for _ in range(5):
+                g.replay()
+            e1.record(side)
+            torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / (5 * REPS)
+
+    k1_us = [kernel_us(lambda it=it: it["plan"].input_transform(it["x"], it["ws"])) for it in items]
+    k2_us = [kernel_us(lambda it=it: it["plan"].contract_output(it["ws"], it["blob"], it["y"]))
+             for it in items]
+    k3_us = [kernel_us(lambda it=it: it["plan"].weight_prepare(it["w"], it["b"], it["blob"]))
+             for it in items]
 
     per_layer = []
     for k, it in enumerate(items):
@@ -160,7 +196,8 @@ def main():
         dom, dom_bytes, dom_us = "k_input_transform", sum(k1_bytes(it["lay"]) for it in items), tot_k1
     achieved = dom_bytes / (dom_us * 1e-6) / 1e9
     roofline = dict(bound="hbm", kernel=dom, achieved=round(achieved, 1), peak=HBM_PEAK_GBS,
-                    unit="GB/s", frac=round(achieved / HBM_PEAK_GBS, 4), traffic=None,
+                    unit="GB/s", frac=round(achieved / HBM_PEAK_GBS, 4),
+                    traffic=measured_traffic(dom, args.config),
                     algorithmic_bytes_per_step=dom_bytes, avg_launch_us=round(dom_us / len(items), 2),
                     launches_per_step=len(items))
 
@@ -205,6 +242,7 @@ def main():
                "(2*N*H*W*Cin*Cout*9 per layer / time); per-layer us in 'layers'",
         value=round(value, 2), unit="TOPS", n_gpus=1, steps=args.steps, warmup=args.warmup,
         ms_per_step=round(sec * 1e3, 4), us_per_layer=round(sec * 1e6 / n_convs, 2),
+        launch="one HIP graph replay per step", eager_ms_per_step=round(sec_eager * 1e3, 4),
         higher_is_better=True, scaling="weak", vs_baseline=None, dtype="int8",
         data="synthetic",
         config=dict(workload=f"configs[{args.config - 1}]: " + "; ".join(l.name for l in layers),

@@ -136,12 +136,8 @@ __global__ __launch_bounds__(64 * (M + 2) * KS) void k_contract_output(const Arg
                 const v2i t = __builtin_amdgcn_raw_buffer_load_b64(rW, vW + no * 16 * Cin, oW, 0);
                 s.a[no] = v4i{t.x, t.y, 0, 0};
             }
-#ifdef WQ_EXP_NOSCALE
-            s.sw[no] = v4f{1.f, 2.f, 3.f, 4.f};
-#else
             s.sw[no] = __builtin_bit_cast(
                 v4f, __builtin_amdgcn_raw_buffer_load_b128(rSW, vSW + no * 64, oSW, 0));
-#endif
         }
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
@@ -151,12 +147,8 @@ __global__ __launch_bounds__(64 * (M + 2) * KS) void k_contract_output(const Arg
                 const v2i t = __builtin_amdgcn_raw_buffer_load_b64(rX, vX + nt * 16 * Cin, oX, 0);
                 s.b[nt] = v4i{t.x, t.y, 0, 0};
             }
-#ifdef WQ_EXP_NOSCALE
-            s.sx[nt] = 0.5f;
-#else
             s.sx[nt] = __builtin_bit_cast(
                 float, __builtin_amdgcn_raw_buffer_load_b32(rSX, vSX + nt * groups * 64, oSX, 0));
-#endif
         }
         oW += stepOp;
         oX += stepOp;
@@ -181,11 +173,7 @@ __global__ __launch_bounds__(64 * (M + 2) * KS) void k_contract_output(const Arg
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) R[b][no][nt] = make_float4(0.f, 0.f, 0.f, 0.f);
 
-#ifdef WQ_EXP_NOKLOOP
-    const int NI = D;
-#else
     const int NI = n * cps;   // >= n >= 4 >= D
-#endif
     Stage<K64, NT, NO> st[D];
 #pragma unroll
     for (int d = 0; d < D; ++d) load_stage(st[d]);
@@ -353,11 +341,7 @@ __global__ __launch_bounds__(64 * (M + 2) * KS) void k_contract_output(const Arg
                     *reinterpret_cast<float4 *>(&Rs[w][bp][l16 * RS_STRIDE + 4 * q]) =
                         R[p * BP + bp][no][nt];
                 __syncthreads();
-#ifdef WQ_EXP_NOFINAL
-                for (int idx = tid; idx < (a.T == -1 ? BP * 256 : 0); idx += NTH) {
-#else
                 for (int idx = tid < NTH ? tid : BP * 256; idx < BP * 256; idx += NTH) {
-#endif
                     const int bp = idx >> 8;   // idx & 255 == tid & 255 for every iteration
                     const int bcol = p * BP + bp;
                     float Yv[M];
@@ -375,11 +359,7 @@ __global__ __launch_bounds__(64 * (M + 2) * KS) void k_contract_output(const Arg
                     }
                     const int hv = out_lim[nt] & 0xff, wv = out_lim[nt] >> 8;
                     const int o = o0 + no * 16 + ol;
-#ifdef WQ_EXP_NOSTORE
-                    if (bcol < wv && o < a.Cout && Yv[0] == 123.456f) {
-#else
                     if (bcol < wv && o < a.Cout) {
-#endif
                         float *dst = a.y + (size_t)out_off[nt] + bcol * a.Cout + o;
 #pragma unroll
                         for (int aa = 0; aa < M; ++aa)
@@ -407,8 +387,7 @@ hipError_t launch_cfg(const Args &a, hipStream_t s) {
     return hipGetLastError();
 }
 
-// Pick a tile configuration from the problem size: the largest block that still
-// leaves every CU with work, and a K split when even 16x16 blocks are too few.
+// Pick a tile configuration from the problem size.
 inline int choose_cfg(const wq_plan *p) {
     if (!p->sparse_at || p->m == 2 || p->g > 64) return CFG_BASE;
     // tuning knob: WQ_K2_CONFIG=0..3 forces a configuration where it is applicable
@@ -417,12 +396,14 @@ inline int choose_cfg(const wq_plan *p) {
         if (c == CFG_KSPLIT && p->groups % 2 != 0) return CFG_BASE;
         if (c >= CFG_BASE && c <= CFG_BIG) return c;
     }
+    // Measured on MI355X over the ResNet / UNet layer shapes (tile blocks tb, channel blocks ob):
+    // few tile blocks -> split K over more waves; many blocks -> taller or bigger register tiles.
     const long tb = p->T_pad / 16, ob = p->Cout_pad / 16;
-    if ((tb / 2) * (ob / 2) >= 512) return CFG_BIG;
-    if ((tb / 2) * ob >= 384) return CFG_TALL;
-    if (tb * ob >= 512) return CFG_BASE;
-    if (p->groups % 2 == 0 && p->groups >= 4) return CFG_KSPLIT;
-    return CFG_BASE;
+    const bool can_split = p->groups % 2 == 0 && p->groups >= 4;
+    if (tb <= 2) return can_split ? CFG_KSPLIT : CFG_BASE;
+    if (tb * ob >= 640) return ob >= 40 ? CFG_BIG : CFG_TALL;
+    if (tb >= 16) return CFG_TALL;
+    return (can_split && p->groups >= 16) ? CFG_KSPLIT : CFG_BASE;
 }
 
 // fp64 chunk totals only where a wave reduces more than 8 groups per tap

@@ -174,3 +174,38 @@ def test_config_layers_full_size(wq, cfg, idx):
     n2 = lay.n ** 2
     p_bytes = n2 * lay.tiles * (lay.Cin // lay.group_size) * lay.Cout * 4
     check(wq, d, want_P=p_bytes <= 300 << 20)
+
+
+def test_graph_replay_matches_eager(wq):
+    """The forward pass captured in a HIP graph and replayed several times, with
+    eager work and synchronisations in between, gives the eager result bit for bit."""
+    d = workloads.small_layer(51, 2, 13, 11, 64, 48, 6, 32)
+    lay = d.layer
+    plan = wq.Plan(lay.N, lay.H, lay.W, lay.Cin, lay.Cout, lay.m, lay.group_size)
+    blob, ws = plan.alloc_blob(), plan.alloc_workspace()
+    x = torch.from_numpy(d.x).cuda()
+    plan.weight_prepare(torch.from_numpy(d.w).cuda(), torch.from_numpy(d.bias).cuda(), blob)
+    y_eager = plan.alloc_output()
+    plan.forward(x, blob, ws, y_eager)
+    torch.cuda.synchronize()
+    want = y_eager.clone()
+    y = plan.alloc_output()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        plan.forward(x, blob, ws, y)
+        side.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            plan.forward(x, blob, ws, y)
+    torch.cuda.synchronize()
+    for k in range(4):
+        y.fill_(float("nan"))
+        ws.zero_()                                   # eager work between replays
+        torch.cuda.synchronize()
+        with torch.cuda.stream(side):
+            g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y, want), f"replay {k}"
+        plan.forward(x, blob, ws, y_eager)           # eager run of the same plan in between
+        torch.cuda.synchronize()
+        assert torch.equal(y_eager, want)

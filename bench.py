@@ -67,6 +67,11 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=2, help="layer set 1..5 (2 = the headline one)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--eager", action="store_true",
+                    help="launch the step from Python instead of replaying a HIP graph (for profilers)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a 256 MiB device-to-device copy three times (known HBM traffic, "
+                         "used to calibrate the FETCH_SIZE / WRITE_SIZE counters) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
@@ -80,6 +85,14 @@ def main():
     wq.lib()   # fails loudly when the HIP library is missing; there is no fallback
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.copy_calibration:
+        src = torch.ones(64 << 20, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": src.numel() * 4, "copy_bytes_written": src.numel() * 4}))
+        return
     stream = torch.cuda.current_stream()
 
     layers = workloads.CONFIGS[args.config]
@@ -132,8 +145,18 @@ def main():
             torch.cuda.synchronize()
             return (time.perf_counter() - t0) / steps
 
-    g_step = capture(step)
-    sec = timed_replays(g_step, args.steps, args.warmup)
+    if args.eager:
+        for _ in range(args.warmup):
+            step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        sec = (time.perf_counter() - t0) / args.steps
+    else:
+        g_step = capture(step)
+        sec = timed_replays(g_step, args.steps, args.warmup)
     n_convs = len(items)
     direct_ops = sum(it['lay'].direct_ops for it in items)
     value = direct_ops / sec / 1e12
@@ -242,7 +265,7 @@ def main():
                "(2*N*H*W*Cin*Cout*9 per layer / time); per-layer us in 'layers'",
         value=round(value, 2), unit="TOPS", n_gpus=1, steps=args.steps, warmup=args.warmup,
         ms_per_step=round(sec * 1e3, 4), us_per_layer=round(sec * 1e6 / n_convs, 2),
-        launch="one HIP graph replay per step", eager_ms_per_step=round(sec_eager * 1e3, 4),
+        launch="eager launches from Python" if args.eager else "one HIP graph replay per step", eager_ms_per_step=round(sec_eager * 1e3, 4),
         higher_is_better=True, scaling="weak", vs_baseline=None, dtype="int8",
         data="synthetic",
         config=dict(workload=f"configs[{args.config - 1}]: " + "; ".join(l.name for l in layers),

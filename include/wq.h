@@ -54,6 +54,7 @@ typedef struct wq_plan wq_plan_t; /* opaque host object */
  *                 bias fp32 [Cout_pad]             at blob_bias_off
  *   workspace   : Xq int8, blocked            at ws_Xq_off
  *                 sX fp32 [n*n][T_pad/16][groups][16]  at ws_sX_off  (last index = tile % 16)
+ *                 M  fp32 [T_pad][n*n][Cout_pad]       at ws_M_off   (scratch of the two-kernel path)
  *   debug dump  : P int32 [n*n][T][groups][Cout]   (dense, no padding)
  * Blocked int8 layout (R = T_pad for Xq, Cout_pad for Wq; the MFMA operand order):
  *   [n*n][R/16][Cin/kstep][4][16][kstep/4]
@@ -65,7 +66,7 @@ typedef struct {
     int32_t N, H, W, Cin, Cout, m, n, group_size, groups;
     int32_t TH, TW, T, T_pad, Cout_pad, kstep;
     uint64_t blob_bytes, blob_Wq_off, blob_sW_off, blob_bias_off;
-    uint64_t ws_bytes, ws_Xq_off, ws_sX_off;
+    uint64_t ws_bytes, ws_Xq_off, ws_sX_off, ws_M_off;
     uint64_t debug_P_bytes;
 } wq_layout_t;
 
@@ -104,9 +105,10 @@ wq_status_t wq_input_transform(const wq_plan_t *plan, void *stream, const float 
 
 /* Stages 2+3 alone (int8 contraction with per-group dequantization, then
  * y = A^T Y A + bias): reads the workspace written by wq_input_transform and
- * the weight blob, writes y_dev [N][H][W][Cout] fp32. */
+ * the weight blob, writes y_dev [N][H][W][Cout] fp32.  May use the M scratch area of
+ * the workspace. */
 wq_status_t wq_contract_output(const wq_plan_t *plan, void *stream,
-                               const void *workspace_dev, size_t workspace_bytes,
+                               void *workspace_dev, size_t workspace_bytes,
                                const void *weight_blob_dev, size_t blob_bytes, float *y_dev);
 
 /* The whole forward pass: wq_input_transform followed by wq_contract_output. */

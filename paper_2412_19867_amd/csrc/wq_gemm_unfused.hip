@@ -1,0 +1,299 @@
+// Stages 2 and 3 as two kernels, for layers whose Winograd-domain result
+// M [taps][tiles][Cout] (fp32) is small next to their operands: few tiles,
+// many channels.  There the fused kernel's register tiles re-read each operand
+// block from L2 many times and too few workgroups stream the weights; a
+// conventional LDS-tiled GEMM per tap reads every operand block once per
+// 64x64 output tile, and M is written once and read once.
+//
+//   k_gemm_dequant      grid (Cout/64, tiles/64, taps), 4 waves.  Per K-step the
+//                       256 threads copy four 16-row weight blocks and four
+//                       16-row activation blocks (already in MFMA operand
+//                       order) plus the 64+64 scales of the group into LDS,
+//                       double buffered; every wave owns a 32x32 quarter
+//                       (2x2 int8 MFMA blocks, fresh int32 accumulators per
+//                       group) and dequantizes into fp32 at each group end.
+//   k_output_transform  one thread per (tile, channel): y = A^T M A + bias,
+//                       a tap row at a time, NHWC store with the ragged edge masked.
+#include "wq_internal.h"
+
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v2i __attribute__((ext_vector_type(2)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+constexpr int kBufFlags = 0x00020000;
+
+struct GArgs {
+    const int8_t *Xq;
+    const float *sX;
+    const int8_t *Wq;
+    const float *sW;
+    float *Mbuf;
+    int Cin, T_pad, Cout_pad, log2g, n2;
+};
+
+template <bool K64, bool CPG1, bool WIDE>
+__global__ __launch_bounds__(256) void k_gemm_dequant(const GArgs a) {
+    constexpr int KSTEP = K64 ? 64 : 32, KB = KSTEP / 4;
+    constexpr int BLK = 16 * KSTEP;           // bytes of one K-step of a 16-row block
+    constexpr int LPT = 8 * BLK / (256 * 16); // 16-byte loads per thread per K-step
+    __shared__ __attribute__((aligned(16))) char opnd[2][8 * BLK];   // blocks 0-3 weights, 4-7 activations
+    __shared__ __attribute__((aligned(16))) float sc[2][128];        // 64 weight scales, 64 activation scales
+
+    const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15, q = lane >> 4;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6), wm = w >> 1, wn = w & 1;
+    const int t = blockIdx.z, ob0 = blockIdx.x * 4, tb0 = blockIdx.y * 4;   // in 16-row blocks
+    const int Cin = a.Cin, T_pad = a.T_pad, Cout_pad = a.Cout_pad;
+    const int groups = Cin >> a.log2g, cps = Cin / KSTEP;
+    const int cpg_mask = ((1 << a.log2g) / KSTEP) - 1;
+    const unsigned n2 = (unsigned)a.n2;
+
+    const __amdgpu_buffer_rsrc_t rW = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<int8_t *>(a.Wq), 0, (int)(n2 * (unsigned)Cout_pad * (unsigned)Cin), kBufFlags);
+    const __amdgpu_buffer_rsrc_t rX = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<int8_t *>(a.Xq), 0, (int)(n2 * (unsigned)T_pad * (unsigned)Cin), kBufFlags);
+    const __amdgpu_buffer_rsrc_t rSW = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float *>(a.sW), 0, (int)(n2 * (unsigned)groups * (unsigned)Cout_pad * 4u), kBufFlags);
+    const __amdgpu_buffer_rsrc_t rSX = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float *>(a.sX), 0, (int)(n2 * (unsigned)T_pad * (unsigned)groups * 4u), kBufFlags);
+
+    // which 16 bytes of the 8-block stage this thread copies (per load u), as buffer offsets
+    int vop[LPT];
+#pragma unroll
+    for (int u = 0; u < LPT; ++u) {
+        const int c = tid + u * 256, blk = c / (BLK / 16), off = (c % (BLK / 16)) * 16;
+        vop[u] = (blk < 4 ? (ob0 + blk) : (tb0 + blk - 4)) * 16 * Cin + off;
+    }
+    // scales: wave 0 copies the 64 weight scales, wave 1 the 64 activation scales of the group
+    const int vsc = w == 0 ? (ob0 * 16 + lane) * 4
+                           : ((tb0 + (lane >> 4)) * groups * 64 + (lane & 15) * 4);
+    const unsigned baseW = (unsigned)t * Cout_pad * Cin, baseX = (unsigned)t * T_pad * Cin;
+    const unsigned baseSW = (unsigned)t * groups * Cout_pad * 4, baseSX = (unsigned)t * T_pad * groups * 4;
+
+    // K-step s+1 is fetched into registers while step s is consumed from LDS buffer s & 1,
+    // then moved to the other buffer.  (Deeper register rings were measured: no gain.)
+    v4i pre[LPT];
+    float psc;
+    auto fetch = [&](int s, v4i (&dst)[LPT], float &dsc) {   // global -> registers for K-step s
+#pragma unroll
+        for (int u = 0; u < LPT; ++u) {
+            // K32: threads 0-127 (waves 0,1) copy weights; K64: load 0 copies weights, load 1 activations
+            const bool isW = K64 ? (u == 0) : (w < 2);
+            dst[u] = isW ? __builtin_amdgcn_raw_buffer_load_b128(rW, vop[u], baseW + (unsigned)s * BLK, 0)
+                         : __builtin_amdgcn_raw_buffer_load_b128(rX, vop[u], baseX + (unsigned)s * BLK, 0);
+        }
+        const unsigned gam = (unsigned)(s * KSTEP) >> a.log2g;
+        dsc = 0.f;
+        if (w == 0)
+            dsc = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
+                                                rSW, vsc, baseSW + gam * (unsigned)Cout_pad * 4u, 0));
+        else if (w == 1)
+            dsc = __builtin_bit_cast(float,
+                                     __builtin_amdgcn_raw_buffer_load_b32(rSX, vsc, baseSX + gam * 64u, 0));
+    };
+    auto commit = [&](int buf, const v4i (&src)[LPT], float ssc) {   // registers -> LDS
+#pragma unroll
+        for (int u = 0; u < LPT; ++u)
+            *reinterpret_cast<v4i *>(&opnd[buf][(tid + u * 256) * 16]) = src[u];
+        if (w < 2) sc[buf][w * 64 + lane] = ssc;
+    };
+
+    v4i acc[2][2];
+    float4 Mc[2][2];
+    double Mt[2][2][4];
+#pragma unroll
+    for (int no = 0; no < 2; ++no)
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) {
+            acc[no][nt] = v4i{0, 0, 0, 0};
+            Mc[no][nt] = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) Mt[no][nt][r] = 0.0;
+        }
+    int in_chunk = 0;
+
+    fetch(0, pre, psc);
+    commit(0, pre, psc);
+    __syncthreads();
+    for (int s = 0; s < cps; ++s) {
+        const int buf = s & 1;
+        if (s + 1 < cps) fetch(s + 1, pre, psc);
+        // operands of this wave's 2x2 blocks
+        v4i av[2], bv[2];
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            const char *pa = &opnd[buf][(2 * wn + e) * BLK + lane * KB];
+            const char *pb = &opnd[buf][(4 + 2 * wm + e) * BLK + lane * KB];
+            if constexpr (K64) {
+                av[e] = *reinterpret_cast<const v4i *>(pa);
+                bv[e] = *reinterpret_cast<const v4i *>(pb);
+            } else {
+                const v2i ta = *reinterpret_cast<const v2i *>(pa), tb = *reinterpret_cast<const v2i *>(pb);
+                av[e] = v4i{ta.x, ta.y, 0, 0};
+                bv[e] = v4i{tb.x, tb.y, 0, 0};
+            }
+        }
+#pragma unroll
+        for (int no = 0; no < 2; ++no)
+#pragma unroll
+            for (int nt = 0; nt < 2; ++nt) {
+                const v4i c0 = CPG1 ? v4i{0, 0, 0, 0} : acc[no][nt];
+                if constexpr (K64) {
+                    acc[no][nt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(av[no], bv[nt], c0, 0, 0, 0);
+                } else {
+                    const long x = __builtin_bit_cast(long, v2i{av[no].x, av[no].y});
+                    const long y = __builtin_bit_cast(long, v2i{bv[nt].x, bv[nt].y});
+                    acc[no][nt] = __builtin_amdgcn_mfma_i32_16x16x32_i8(x, y, c0, 0, 0, 0);
+                }
+            }
+        if (CPG1 || ((s + 1) & cpg_mask) == 0) {   // last K-step of a group: dequantize
+#pragma unroll
+            for (int no = 0; no < 2; ++no) {
+                const v4f sw = *reinterpret_cast<const v4f *>(&sc[buf][(2 * wn + no) * 16 + 4 * q]);
+#pragma unroll
+                for (int nt = 0; nt < 2; ++nt) {
+                    const float sx = sc[buf][64 + (2 * wm + nt) * 16 + l16];
+                    Mc[no][nt].x = __builtin_fmaf((float)acc[no][nt][0], sw.x * sx, Mc[no][nt].x);
+                    Mc[no][nt].y = __builtin_fmaf((float)acc[no][nt][1], sw.y * sx, Mc[no][nt].y);
+                    Mc[no][nt].z = __builtin_fmaf((float)acc[no][nt][2], sw.z * sx, Mc[no][nt].z);
+                    Mc[no][nt].w = __builtin_fmaf((float)acc[no][nt][3], sw.w * sx, Mc[no][nt].w);
+                    if constexpr (!CPG1) acc[no][nt] = v4i{0, 0, 0, 0};
+                }
+            }
+            if (WIDE && ++in_chunk == 4) {   // fp64 totals of 4-group fp32 chunks (long reductions)
+                in_chunk = 0;
+#pragma unroll
+                for (int no = 0; no < 2; ++no)
+#pragma unroll
+                    for (int nt = 0; nt < 2; ++nt) {
+                        Mt[no][nt][0] += (double)Mc[no][nt].x;
+                        Mt[no][nt][1] += (double)Mc[no][nt].y;
+                        Mt[no][nt][2] += (double)Mc[no][nt].z;
+                        Mt[no][nt][3] += (double)Mc[no][nt].w;
+                        Mc[no][nt] = make_float4(0.f, 0.f, 0.f, 0.f);
+                    }
+            }
+        }
+        if (s + 1 < cps) commit(buf ^ 1, pre, psc);
+        __syncthreads();
+    }
+    // store M [tile][tap][Cout_pad] (a tile's taps together: the output transform reads them
+    // from one contiguous region); the lane holds channels 4q..4q+3 of tile l16 in each block
+#pragma unroll
+    for (int no = 0; no < 2; ++no)
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) {
+            float4 Mv = Mc[no][nt];
+            if constexpr (WIDE)
+                Mv = make_float4((float)(Mt[no][nt][0] + (double)Mv.x), (float)(Mt[no][nt][1] + (double)Mv.y),
+                                 (float)(Mt[no][nt][2] + (double)Mv.z), (float)(Mt[no][nt][3] + (double)Mv.w));
+            const int tau = (tb0 + 2 * wm + nt) * 16 + l16, o = (ob0 + 2 * wn + no) * 16 + 4 * q;
+            if (tau < T_pad && o < Cout_pad)
+                *reinterpret_cast<float4 *>(a.Mbuf + ((size_t)tau * n2 + t) * Cout_pad + o) = Mv;
+        }
+}
+
+struct OArgs {
+    wq_xf xf;
+    const float *Mbuf;
+    const float *bias;
+    float *y;
+    int H, W, Cout, TH, TW, T, T_pad, Cout_pad;
+};
+
+template <int M, bool ATSP>
+__global__ __launch_bounds__(256) void k_output_transform(const OArgs a) {
+    constexpr int n = M + 2;
+    using Pat = wq_pattern<M>;
+    const int o = blockIdx.x * 64 + (threadIdx.x & 63);
+    const int tau = blockIdx.y * 4 + (threadIdx.x >> 6);
+    if (o >= a.Cout || tau >= a.T) return;
+    const size_t plane = (size_t)a.Cout_pad;   // M [tile][tap][Cout_pad]
+    const float *src = a.Mbuf + (size_t)tau * (n * n) * a.Cout_pad + o;
+    // all n*n loads first (one exposed memory latency instead of n), then the arithmetic
+    float Mv[n][n];
+#pragma unroll
+    for (int i = 0; i < n; ++i)
+#pragma unroll
+        for (int j = 0; j < n; ++j) Mv[i][j] = src[(size_t)(i * n + j) * plane];
+    float Y[M][M];
+#pragma unroll
+    for (int aa = 0; aa < M; ++aa)
+#pragma unroll
+        for (int b = 0; b < M; ++b) Y[aa][b] = 0.f;
+#pragma unroll
+    for (int i = 0; i < n; ++i) {
+        const float (&Mrow)[n] = Mv[i];
+        float R[M];
+#pragma unroll
+        for (int b = 0; b < M; ++b) {
+            float r = 0.f;
+#pragma unroll
+            for (int j = 0; j < n; ++j)
+                if (!ATSP || Pat::at(b, j)) r = __builtin_fmaf(a.xf.AT[b * n + j], Mrow[j], r);
+            R[b] = r;
+        }
+#pragma unroll
+        for (int aa = 0; aa < M; ++aa)
+            if (!ATSP || Pat::at(aa, i)) {
+#pragma unroll
+                for (int b = 0; b < M; ++b) Y[aa][b] = __builtin_fmaf(a.xf.AT[aa * n + i], R[b], Y[aa][b]);
+            }
+    }
+    const int tw = tau % a.TW, th = (tau / a.TW) % a.TH, bb = tau / (a.TW * a.TH);
+    const int hv = min(M, a.H - th * M), wv = min(M, a.W - tw * M);
+    const float bv = a.bias[o];
+    float *dst = a.y + ((size_t)(bb * a.H + th * M) * a.W + tw * M) * a.Cout + o;
+#pragma unroll
+    for (int aa = 0; aa < M; ++aa)
+#pragma unroll
+        for (int b = 0; b < M; ++b)
+            if (aa < hv && b < wv) dst[((size_t)aa * a.W + b) * a.Cout] = Y[aa][b] + bv;
+}
+
+template <bool K64, bool CPG1>
+void launch_gemm(const GArgs &g, dim3 grid, hipStream_t s, bool wide) {
+    if (wide)
+        hipLaunchKernelGGL((k_gemm_dequant<K64, CPG1, true>), grid, dim3(256), 0, s, g);
+    else
+        hipLaunchKernelGGL((k_gemm_dequant<K64, CPG1, false>), grid, dim3(256), 0, s, g);
+}
+
+template <int M>
+void launch_out(const OArgs &o, dim3 grid, hipStream_t s, bool atsp) {
+    if (atsp)
+        hipLaunchKernelGGL((k_output_transform<M, true>), grid, dim3(256), 0, s, o);
+    else
+        hipLaunchKernelGGL((k_output_transform<M, false>), grid, dim3(256), 0, s, o);
+}
+
+}  // namespace
+
+hipError_t wq_launch_contract_unfused(const wq_plan *p, hipStream_t s, const int8_t *Xq, const float *sX,
+                                      const int8_t *Wq, const float *sW, const float *bias, float *Mbuf,
+                                      float *y) {
+    GArgs g;
+    g.Xq = Xq; g.sX = sX; g.Wq = Wq; g.sW = sW; g.Mbuf = Mbuf;
+    g.Cin = p->Cin; g.T_pad = p->T_pad; g.Cout_pad = p->Cout_pad; g.n2 = p->n * p->n;
+    g.log2g = 0;
+    while ((1 << g.log2g) < p->g) ++g.log2g;
+    const dim3 grid((p->Cout_pad + 63) / 64, (p->T_pad + 63) / 64, p->n * p->n);
+    const bool k64 = p->kstep == 64, cpg1 = p->g == p->kstep, wide = p->groups > 8;
+    if (!k64) launch_gemm<false, true>(g, grid, s, wide);
+    else if (cpg1) launch_gemm<true, true>(g, grid, s, wide);
+    else launch_gemm<true, false>(g, grid, s, wide);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+
+    OArgs o;
+    o.xf = p->xf; o.Mbuf = Mbuf; o.bias = bias; o.y = y;
+    o.H = p->H; o.W = p->W; o.Cout = p->Cout; o.TH = p->TH; o.TW = p->TW; o.T = p->T;
+    o.T_pad = p->T_pad; o.Cout_pad = p->Cout_pad;
+    const dim3 ogrid((p->Cout + 63) / 64, (p->T + 3) / 4);
+    switch (p->m) {
+        case 2: launch_out<2>(o, ogrid, s, p->sparse_at); break;
+        case 4: launch_out<4>(o, ogrid, s, p->sparse_at); break;
+        default: launch_out<6>(o, ogrid, s, p->sparse_at); break;
+    }
+    return hipGetLastError();
+}

@@ -3,6 +3,7 @@
 // their arguments and enqueue the kernels.  Nothing here touches the device
 // except through the launchers in the kernel files.
 #include <cmath>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 
@@ -155,7 +156,7 @@ wq_status_t wq_plan_create(wq_plan_t **out, int N, int H, int W, int Cin, int Co
         const long long n2 = (long long)n * n, Tp = (T + 31) / 32 * 32, Cp = (Cout + 31) / 32 * 32;
         const long long lim = (1LL << 31) - 1;
         if ((long long)N * H * W * Cin * 4 > (1LL << 30) || (long long)N * H * W * Cout * 4 > lim ||
-            n2 * Tp * Cin > lim || n2 * Cp * Cin > lim || n2 * Tp * (Cin / group_size) * 4 > lim ||
+            n2 * Tp * Cin > lim || n2 * Cp * Cin > lim || n2 * Tp * Cp * 4 > lim || n2 * Tp * (Cin / group_size) * 4 > lim ||
             n2 * Cp * (Cin / group_size) * 4 > lim)
             return WQ_ERR_UNSUPPORTED;
     }
@@ -168,6 +169,14 @@ wq_status_t wq_plan_create(wq_plan_t **out, int N, int H, int W, int Cin, int Co
     p->T_pad = (int)((T + 31) / 32 * 32);
     p->Cout_pad = (Cout + 31) / 32 * 32;
     p->kstep = group_size == 32 ? 32 : 64;
+    // Path for stages 2+3 (measured on MI355X): with few tiles the Winograd-domain result is
+    // small next to the operands, and a tiled GEMM per tap plus a separate output transform
+    // beats the fused kernel.  WQ_K2_PATH=fused|split overrides.
+    p->two_kernel = p->T_pad <= 512 && (Cin >= 512 || group_size == 32);
+    if (const char *e = std::getenv("WQ_K2_PATH")) {
+        if (!std::strcmp(e, "fused")) p->two_kernel = false;
+        if (!std::strcmp(e, "split")) p->two_kernel = true;
+    }
     p->prepared.store(0);
     std::memset(&p->xf, 0, sizeof(p->xf));
     if (all) {
@@ -201,7 +210,8 @@ wq_status_t wq_plan_create(wq_plan_t **out, int N, int H, int W, int Cin, int Co
     L.blob_bytes = L.blob_bias_off + align256((uint64_t)p->Cout_pad * 4);
     L.ws_Xq_off = 0;
     L.ws_sX_off = align256(n2 * p->T_pad * Cin);
-    L.ws_bytes = L.ws_sX_off + align256(n2 * p->T_pad * p->groups * 4);
+    L.ws_M_off = L.ws_sX_off + align256(n2 * p->T_pad * p->groups * 4);
+    L.ws_bytes = L.ws_M_off + align256(n2 * p->T_pad * p->Cout_pad * 4);
     L.debug_P_bytes = n2 * (uint64_t)T * p->groups * Cout * 4;
     *out = p;
     return WQ_OK;
@@ -246,23 +256,23 @@ wq_status_t wq_input_transform(const wq_plan_t *plan, void *stream, const float 
     return e == hipSuccess ? WQ_OK : WQ_ERR_DEVICE;
 }
 
-static wq_status_t contract_impl(const wq_plan_t *plan, void *stream, const void *workspace_dev,
+static wq_status_t contract_impl(const wq_plan_t *plan, void *stream, void *workspace_dev,
                                  size_t workspace_bytes, const void *weight_blob_dev,
                                  size_t blob_bytes, float *y_dev, int32_t *P_dev) {
     if (!plan || !y_dev) return WQ_ERR_INVALID_ARG;
     wq_status_t st = check_buffers(plan, weight_blob_dev, blob_bytes, workspace_dev, workspace_bytes);
     if (st != WQ_OK) return st;
     if (!plan->prepared.load()) return WQ_ERR_NOT_PREPARED;
-    const char *ws = (const char *)workspace_dev;
+    char *ws = (char *)workspace_dev;
     Blob bl = blob_of(plan, weight_blob_dev);
     hipError_t e = wq_launch_contract(plan, (hipStream_t)stream,
                                       (const int8_t *)(ws + plan->lay.ws_Xq_off),
                                       (const float *)(ws + plan->lay.ws_sX_off), bl.Wq, bl.sW,
-                                      bl.bias, y_dev, P_dev);
+                                      bl.bias, (float *)(ws + plan->lay.ws_M_off), y_dev, P_dev);
     return e == hipSuccess ? WQ_OK : WQ_ERR_DEVICE;
 }
 
-wq_status_t wq_contract_output(const wq_plan_t *plan, void *stream, const void *workspace_dev,
+wq_status_t wq_contract_output(const wq_plan_t *plan, void *stream, void *workspace_dev,
                                size_t workspace_bytes, const void *weight_blob_dev,
                                size_t blob_bytes, float *y_dev) {
     return contract_impl(plan, stream, workspace_dev, workspace_bytes, weight_blob_dev, blob_bytes,

@@ -25,6 +25,8 @@ struct wq_plan {
     // (always the case for diagonal rescalings of the standard matrices), so
     // that kernels may skip those terms of the fused-multiply-add chains.
     bool sparse_bt, sparse_g, sparse_at;
+    // stages 2+3 as GEMM + separate output transform (few tiles, many channels) instead of fused
+    bool two_kernel;
     wq_layout_t lay;
     std::atomic<int> prepared;
 };
@@ -46,6 +48,10 @@ struct wq_pattern {
 hipError_t wq_launch_weight(const wq_plan *p, hipStream_t s, const float *w, const float *bias,
                             int8_t *Wq, float *sW, float *bias_out);
 hipError_t wq_launch_input(const wq_plan *p, hipStream_t s, const float *x, int8_t *Xq, float *sX);
+// Mbuf: fp32 scratch [T_pad][taps][Cout_pad] inside the workspace, used by the two-kernel path
 hipError_t wq_launch_contract(const wq_plan *p, hipStream_t s, const int8_t *Xq, const float *sX,
-                              const int8_t *Wq, const float *sW, const float *bias, float *y,
-                              int32_t *P);
+                              const int8_t *Wq, const float *sW, const float *bias, float *Mbuf,
+                              float *y, int32_t *P);
+hipError_t wq_launch_contract_unfused(const wq_plan *p, hipStream_t s, const int8_t *Xq,
+                                      const float *sX, const int8_t *Wq, const float *sW,
+                                      const float *bias, float *Mbuf, float *y);

@@ -16,10 +16,10 @@
 //            stores s; r goes through LDS;
 //   phase C  every lane quantizes its values as rint(v*r) (rounded product,
 //            then round-half-even via the 1.5*2^23 add) and stores two codes.
-// The input kernel additionally splits the n tap rows over blockIdx.y (two
-// rows per workgroup): B^T d only has to be formed for those rows, so the
-// split costs nothing but re-reading the tile through L1, and it quarters the
-// length of the per-wave instruction stream, which is what bounds this kernel.
+// The input kernel additionally splits the n tap rows in two halves over
+// blockIdx.y: B^T d only has to be formed for the workgroup's rows, so the
+// split costs nothing but re-reading the tile through L1, and it halves the
+// registers and the length of the per-wave instruction stream.
 // The arithmetic order is part of the library's contract: the int8 codes and
 // scales are reproducible bit for bit from the definition in include/wq.h.
 #include <float.h>
@@ -110,7 +110,9 @@ __device__ __forceinline__ void quantize_and_store(const float2 (&vals)[NT], uin
 }
 
 // ---------------------------------------------------------------- stage 1
-constexpr int TR = 2;   // tap rows per workgroup of the input kernel
+// tap rows per workgroup of the input kernel: half of them (measured best of n, n/2, n/4, 1)
+template <int M>
+constexpr int tap_rows_per_wg() { return (M + 2) / 2; }
 
 template <int M, int I0, bool SPARSE>
 __device__ __forceinline__ void input_body(const wq_xf &xf, const float *__restrict__ x,
@@ -118,7 +120,7 @@ __device__ __forceinline__ void input_body(const wq_xf &xf, const float *__restr
                                            int W, int Cin, int TH, int TW, int T, int T_pad,
                                            int log2k, int kstep_log2, unsigned x_bytes,
                                            uint32_t (*amax_s)[16], float (*r_s)[16]) {
-    constexpr int n = M + 2, NT = TR * n;
+    constexpr int n = M + 2, TR = tap_rows_per_wg<M>(), NT = TR * n;
     using Pat = wq_pattern<M>;
     const int tid = threadIdx.x, row = tid >> 4, l16 = tid & 15;
     const int k = 1 << log2k;
@@ -210,23 +212,16 @@ __global__ __launch_bounds__(256) void k_input_transform(wq_xf xf, const float *
                                                          int Cin, int TH, int TW, int T, int T_pad,
                                                          int log2k, int kstep_log2,
                                                          unsigned x_bytes) {
-    constexpr int n = M + 2;
+    constexpr int n = M + 2, TR = tap_rows_per_wg<M>();
     __shared__ uint32_t amax_s[TR * n][16];
     __shared__ float r_s[TR * n][16];
 #define WQ_BODY(I0)                                                                            \
     input_body<M, (I0), SPARSE>(xf, x, Xq, sX, H, W, Cin, TH, TW, T, T_pad, log2k, kstep_log2, \
                                 x_bytes, amax_s, r_s)
-    const int split = blockIdx.y;   // uniform: tap rows 2*split, 2*split+1
-    if (split == 0) {
+    if (blockIdx.y == 0) {   // uniform: the first or the second half of the tap rows
         WQ_BODY(0);
-    } else if (split == 1) {
-        WQ_BODY(2);
-    } else if constexpr (n >= 6) {
-        if (split == 2) {
-            WQ_BODY(4);
-        } else if constexpr (n >= 8) {
-            WQ_BODY(6);
-        }
+    } else {
+        WQ_BODY(TR);
     }
 #undef WQ_BODY
 }
@@ -323,7 +318,7 @@ int ilog2(int v) {
 
 template <int M>
 hipError_t launch_input_m(const wq_plan *p, hipStream_t s, const float *x, int8_t *Xq, float *sX) {
-    const dim3 grid((unsigned)((p->T_pad / 16) * (p->Cin / 32)), (M + 2) / TR), block(256);
+    const dim3 grid((unsigned)((p->T_pad / 16) * (p->Cin / 32)), 2), block(256);
     const int log2k = ilog2(p->g / 32), kstep_log2 = p->kstep == 32 ? 5 : 6;
     const unsigned x_bytes = (unsigned)((size_t)p->N * p->H * p->W * p->Cin * 4);
     if (p->sparse_bt)

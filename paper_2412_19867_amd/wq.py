@@ -30,7 +30,7 @@ class Layout(ctypes.Structure):
                   "TH", "TW", "T", "T_pad", "Cout_pad", "kstep")] +
                 [(k, ctypes.c_uint64) for k in
                  ("blob_bytes", "blob_Wq_off", "blob_sW_off", "blob_bias_off",
-                  "ws_bytes", "ws_Xq_off", "ws_sX_off", "debug_P_bytes")])
+                  "ws_bytes", "ws_Xq_off", "ws_sX_off", "ws_M_off", "debug_P_bytes")])
 
 
 class WqError(RuntimeError):

@@ -12,8 +12,9 @@
 //                       double buffered; every wave owns a 32x32 quarter
 //                       (2x2 int8 MFMA blocks, fresh int32 accumulators per
 //                       group) and dequantizes into fp32 at each group end.
-//   k_output_transform  one thread per (tile, channel): y = A^T M A + bias,
-//                       a tap row at a time, NHWC store with the ragged edge masked.
+//   k_output_transform  one workgroup per (tile, 64 channels), one wave per output
+//                       column: y = A^T M A + bias through LDS, NHWC store with the
+//                       ragged edge masked.
 #include "wq_internal.h"
 
 namespace {
@@ -33,7 +34,7 @@ struct GArgs {
 };
 
 template <bool K64, bool CPG1, bool WIDE>
-__global__ __launch_bounds__(256) void k_gemm_dequant(const GArgs a) {
+__global__ __launch_bounds__(256, 2) void k_gemm_dequant(const GArgs a) {
     constexpr int KSTEP = K64 ? 64 : 32, KB = KSTEP / 4;
     constexpr int BLK = 16 * KSTEP;           // bytes of one K-step of a 16-row block
     constexpr int LPT = 8 * BLK / (256 * 16); // 16-byte loads per thread per K-step
@@ -201,54 +202,53 @@ struct OArgs {
     int H, W, Cout, TH, TW, T, T_pad, Cout_pad;
 };
 
+// One workgroup per (tile, 64 output channels): the tile's n*n x 64 slice of M goes
+// through LDS once, then wave b (one per output column) forms column b of Y A and of
+// A^T (Y A).  Splitting an element's work over M waves keeps several waves on every
+// SIMD even for layers with few tiles; a lone wave per SIMD issues at a fraction of
+// the vector-ALU rate.
 template <int M, bool ATSP>
-__global__ __launch_bounds__(256) void k_output_transform(const OArgs a) {
-    constexpr int n = M + 2;
+__global__ __launch_bounds__(64 * M) void k_output_transform(const OArgs a) {
+    constexpr int n = M + 2, n2 = n * n;
     using Pat = wq_pattern<M>;
-    const int o = blockIdx.x * 64 + (threadIdx.x & 63);
-    const int tau = blockIdx.y * 4 + (threadIdx.x >> 6);
-    if (o >= a.Cout || tau >= a.T) return;
-    const size_t plane = (size_t)a.Cout_pad;   // M [tile][tap][Cout_pad]
-    const float *src = a.Mbuf + (size_t)tau * (n * n) * a.Cout_pad + o;
-    // all n*n loads first (one exposed memory latency instead of n), then the arithmetic
-    float Mv[n][n];
+    __shared__ __attribute__((aligned(16))) float Ms[n2][64];
+    const int tid = threadIdx.x, ol = tid & 63;
+    const int b = __builtin_amdgcn_readfirstlane(tid >> 6);   // output column of this wave
+    const int o0 = blockIdx.x * 64, tau = blockIdx.y;
+    const float *src = a.Mbuf + (size_t)tau * n2 * a.Cout_pad + o0;   // M [tile][tap][Cout_pad]
+    for (int idx = tid; idx < n2 * 16; idx += 64 * M) {
+        const int t = idx >> 4, c4 = (idx & 15) * 4;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (o0 + c4 < a.Cout_pad) v = *reinterpret_cast<const float4 *>(src + (size_t)t * a.Cout_pad + c4);
+        *reinterpret_cast<float4 *>(&Ms[t][c4]) = v;
+    }
+    __syncthreads();
+    float atb[n];
 #pragma unroll
-    for (int i = 0; i < n; ++i)
-#pragma unroll
-        for (int j = 0; j < n; ++j) Mv[i][j] = src[(size_t)(i * n + j) * plane];
-    float Y[M][M];
-#pragma unroll
-    for (int aa = 0; aa < M; ++aa)
-#pragma unroll
-        for (int b = 0; b < M; ++b) Y[aa][b] = 0.f;
+    for (int j = 0; j < n; ++j) atb[j] = a.xf.AT[b * n + j];
+    float R[n];
 #pragma unroll
     for (int i = 0; i < n; ++i) {
-        const float (&Mrow)[n] = Mv[i];
-        float R[M];
+        float r = 0.f;
 #pragma unroll
-        for (int b = 0; b < M; ++b) {
-            float r = 0.f;
-#pragma unroll
-            for (int j = 0; j < n; ++j)
-                if (!ATSP || Pat::at(b, j)) r = __builtin_fmaf(a.xf.AT[b * n + j], Mrow[j], r);
-            R[b] = r;
-        }
-#pragma unroll
-        for (int aa = 0; aa < M; ++aa)
-            if (!ATSP || Pat::at(aa, i)) {
-#pragma unroll
-                for (int b = 0; b < M; ++b) Y[aa][b] = __builtin_fmaf(a.xf.AT[aa * n + i], R[b], Y[aa][b]);
-            }
+        for (int j = 0; j < n; ++j) r = __builtin_fmaf(atb[j], Ms[i * n + j][ol], r);
+        R[i] = r;
     }
+    const int o = o0 + ol;
     const int tw = tau % a.TW, th = (tau / a.TW) % a.TH, bb = tau / (a.TW * a.TH);
     const int hv = min(M, a.H - th * M), wv = min(M, a.W - tw * M);
-    const float bv = a.bias[o];
-    float *dst = a.y + ((size_t)(bb * a.H + th * M) * a.W + tw * M) * a.Cout + o;
+    if (o < a.Cout && b < wv) {
+        const float bv = a.bias[o];
+        float *dst = a.y + ((size_t)(bb * a.H + th * M) * a.W + tw * M + b) * a.Cout + o;
 #pragma unroll
-    for (int aa = 0; aa < M; ++aa)
+        for (int aa = 0; aa < M; ++aa) {
+            float yv = 0.f;
 #pragma unroll
-        for (int b = 0; b < M; ++b)
-            if (aa < hv && b < wv) dst[((size_t)aa * a.W + b) * a.Cout] = Y[aa][b] + bv;
+            for (int i = 0; i < n; ++i)
+                if (!ATSP || Pat::at(aa, i)) yv = __builtin_fmaf(a.xf.AT[aa * n + i], R[i], yv);
+            if (aa < hv) dst[(size_t)aa * a.W * a.Cout] = yv + bv;
+        }
+    }
 }
 
 template <bool K64, bool CPG1>
@@ -262,9 +262,9 @@ void launch_gemm(const GArgs &g, dim3 grid, hipStream_t s, bool wide) {
 template <int M>
 void launch_out(const OArgs &o, dim3 grid, hipStream_t s, bool atsp) {
     if (atsp)
-        hipLaunchKernelGGL((k_output_transform<M, true>), grid, dim3(256), 0, s, o);
+        hipLaunchKernelGGL((k_output_transform<M, true>), grid, dim3(64 * M), 0, s, o);
     else
-        hipLaunchKernelGGL((k_output_transform<M, false>), grid, dim3(256), 0, s, o);
+        hipLaunchKernelGGL((k_output_transform<M, false>), grid, dim3(64 * M), 0, s, o);
 }
 
 }  // namespace
@@ -289,7 +289,7 @@ hipError_t wq_launch_contract_unfused(const wq_plan *p, hipStream_t s, const int
     o.xf = p->xf; o.Mbuf = Mbuf; o.bias = bias; o.y = y;
     o.H = p->H; o.W = p->W; o.Cout = p->Cout; o.TH = p->TH; o.TW = p->TW; o.T = p->T;
     o.T_pad = p->T_pad; o.Cout_pad = p->Cout_pad;
-    const dim3 ogrid((p->Cout + 63) / 64, (p->T + 3) / 4);
+    const dim3 ogrid((p->Cout + 63) / 64, p->T);
     switch (p->m) {
         case 2: launch_out<2>(o, ogrid, s, p->sparse_at); break;
         case 4: launch_out<4>(o, ogrid, s, p->sparse_at); break;

@@ -69,6 +69,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--eager", action="store_true",
                     help="launch the step from Python instead of replaying a HIP graph (for profilers)")
+    ap.add_argument("--only-steps", action="store_true",
+                    help="launch warmup+steps steps eagerly, print the launch count and exit (for counter "
+                         "runs: every dispatch in the process then belongs to a step)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a 256 MiB device-to-device copy three times (known HBM traffic, "
                          "used to calibrate the FETCH_SIZE / WRITE_SIZE counters) and exit")
@@ -120,6 +123,14 @@ def main():
             if with_offline:
                 it["plan"].weight_prepare(it["w"], it["b"], it["blob"])
             it["plan"].forward(it["x"], it["blob"], it["ws"], it["y"])
+
+    if args.only_steps:
+        for _ in range(args.warmup + args.steps):
+            step()
+        torch.cuda.synchronize()
+        print(json.dumps({"steps_launched": args.warmup + args.steps, "convs_per_step": len(items),
+                          "offline_stage_launches": len(items)}))
+        return
 
     side = torch.cuda.Stream()
 
@@ -196,6 +207,10 @@ def main():
              for it in items]
     k3_us = [kernel_us(lambda it=it: it["plan"].weight_prepare(it["w"], it["b"], it["blob"]))
              for it in items]
+    # layers whose stages 2+3 run as two kernels: each kernel on its own
+    split_us = {k: (kernel_us(lambda it=it: it["plan"].contract(it["ws"], it["blob"])),
+                    kernel_us(lambda it=it: it["plan"].output_transform(it["ws"], it["blob"], it["y"])))
+                for k, it in enumerate(items) if it["plan"].layout.k2_kernels == 2}
 
     per_layer = []
     for k, it in enumerate(items):
@@ -208,21 +223,43 @@ def main():
             k2_hbm_frac=round(k2_bytes(lay) / (k2_us[k] * 1e-6) / 1e9 / HBM_PEAK_GBS, 3),
             k2_mfma_frac=round(2 * lay.n ** 2 * lay.tiles * lay.Cin * lay.Cout
                                / (k2_us[k] * 1e-6) / 1e12 / INT8_PEAK_TOPS, 4),
-            k3_us=round(k3_us[k], 2),
+            k2_kernels=it["plan"].layout.k2_kernels, k3_us=round(k3_us[k], 2),
             k3_hbm_frac=round(k3_bytes(lay) / (k3_us[k] * 1e-6) / 1e9 / HBM_PEAK_GBS, 3)))
 
-    # dominant kernel of the step = the contraction+output-transform kernel or the input transform
-    tot_k1, tot_k2 = sum(k1_us), sum(k2_us)
-    if tot_k2 >= tot_k1:
-        dom, dom_bytes, dom_us = "k_contract_output", sum(k2_bytes(it["lay"]) for it in items), tot_k2
-    else:
-        dom, dom_bytes, dom_us = "k_input_transform", sum(k1_bytes(it["lay"]) for it in items), tot_k1
-    achieved = dom_bytes / (dom_us * 1e-6) / 1e9
+    # per-kernel totals over one step.  Stages 2+3 of a layer are one fused kernel or,
+    # for layers with few tiles, a tiled GEMM followed by an output-transform kernel.
+    kernels = {}
+
+    def account(name, us, nbytes, launches):
+        k = kernels.setdefault(name, dict(us=0.0, bytes=0, launches=0))
+        k["us"] += us
+        k["bytes"] += nbytes
+        k["launches"] += launches
+
+    for k, it in enumerate(items):
+        lay = it["lay"]
+        account("k_input_transform", k1_us[k], k1_bytes(lay), 1)
+        if it["plan"].layout.k2_kernels == 1:
+            account("k_contract_output", k2_us[k], k2_bytes(lay), 1)
+        else:
+            # the fp32 product tensor M is written by the GEMM and read back by the transform
+            m_bytes = 4 * lay.n ** 2 * lay.tiles * lay.Cout
+            y_bytes = 4 * lay.N * lay.H * lay.W * lay.Cout
+            account("k_gemm_dequant", split_us[k][0], k2_bytes(lay) - y_bytes + m_bytes, 1)
+            account("k_output_transform", split_us[k][1], m_bytes + y_bytes, 1)
+    dom = max(kernels, key=lambda name: kernels[name]["us"])
+    dk = kernels[dom]
+    achieved = dk["bytes"] / (dk["us"] * 1e-6) / 1e9
     roofline = dict(bound="hbm", kernel=dom, achieved=round(achieved, 1), peak=HBM_PEAK_GBS,
                     unit="GB/s", frac=round(achieved / HBM_PEAK_GBS, 4),
                     traffic=measured_traffic(dom, args.config),
-                    algorithmic_bytes_per_step=dom_bytes, avg_launch_us=round(dom_us / len(items), 2),
-                    launches_per_step=len(items))
+                    algorithmic_bytes_per_step=dk["bytes"],
+                    avg_launch_us=round(dk["us"] / dk["launches"], 2),
+                    launches_per_step=dk["launches"],
+                    kernels={name: dict(us_per_step=round(v["us"], 2), launches=v["launches"],
+                                        algorithmic_bytes=v["bytes"],
+                                        hbm_frac=round(v["bytes"] / (v["us"] * 1e-6) / 1e9 / HBM_PEAK_GBS, 4))
+                             for name, v in kernels.items()})
 
     cpu_baseline = None
     if not args.no_cpu_baseline:

@@ -65,6 +65,7 @@ typedef struct wq_plan wq_plan_t; /* opaque host object */
 typedef struct {
     int32_t N, H, W, Cin, Cout, m, n, group_size, groups;
     int32_t TH, TW, T, T_pad, Cout_pad, kstep;
+    int32_t k2_kernels; /* launches of wq_contract_output: 1 = fused kernel, 2 = GEMM + output transform */
     uint64_t blob_bytes, blob_Wq_off, blob_sW_off, blob_bias_off;
     uint64_t ws_bytes, ws_Xq_off, ws_sX_off, ws_M_off;
     uint64_t debug_P_bytes;
@@ -110,6 +111,19 @@ wq_status_t wq_input_transform(const wq_plan_t *plan, void *stream, const float 
 wq_status_t wq_contract_output(const wq_plan_t *plan, void *stream,
                                void *workspace_dev, size_t workspace_bytes,
                                const void *weight_blob_dev, size_t blob_bytes, float *y_dev);
+
+/* Stage 2 alone, in the two-kernel form (any plan may call it, whatever
+ * k2_kernels says): the n*n int8 GEMMs over the workspace's Xq/sX and the
+ * blob's Wq/sW with per-group dequantization (the paper's Eq. 5 with the
+ * scales of Eq. 15); writes M fp32 [T_pad][n*n][Cout_pad] at ws_M_off. */
+wq_status_t wq_contract(const wq_plan_t *plan, void *stream, void *workspace_dev,
+                        size_t workspace_bytes, const void *weight_blob_dev, size_t blob_bytes);
+
+/* Stage 3 alone (the paper's Eq. 6): y = A^T M A + bias from the M that
+ * wq_contract left in the workspace; writes y_dev [N][H][W][Cout] fp32. */
+wq_status_t wq_output_transform(const wq_plan_t *plan, void *stream, const void *workspace_dev,
+                                size_t workspace_bytes, const void *weight_blob_dev,
+                                size_t blob_bytes, float *y_dev);
 
 /* The whole forward pass: wq_input_transform followed by wq_contract_output. */
 wq_status_t wq_conv_forward(const wq_plan_t *plan, void *stream, const float *x_dev,

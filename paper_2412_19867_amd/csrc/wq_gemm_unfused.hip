@@ -271,7 +271,8 @@ void launch_out(const OArgs &o, dim3 grid, hipStream_t s, bool atsp) {
 
 hipError_t wq_launch_contract_unfused(const wq_plan *p, hipStream_t s, const int8_t *Xq, const float *sX,
                                       const int8_t *Wq, const float *sW, const float *bias, float *Mbuf,
-                                      float *y) {
+                                      float *y, int stages) {
+    if (stages & 1) {
     GArgs g;
     g.Xq = Xq; g.sX = sX; g.Wq = Wq; g.sW = sW; g.Mbuf = Mbuf;
     g.Cin = p->Cin; g.T_pad = p->T_pad; g.Cout_pad = p->Cout_pad; g.n2 = p->n * p->n;
@@ -284,6 +285,8 @@ hipError_t wq_launch_contract_unfused(const wq_plan *p, hipStream_t s, const int
     else launch_gemm<true, false>(g, grid, s, wide);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
+    }
+    if (!(stages & 2)) return hipSuccess;
 
     OArgs o;
     o.xf = p->xf; o.Mbuf = Mbuf; o.bias = bias; o.y = y;

@@ -203,6 +203,7 @@ wq_status_t wq_plan_create(wq_plan_t **out, int N, int H, int W, int Cin, int Co
     L.group_size = group_size; L.groups = p->groups;
     L.TH = p->TH; L.TW = p->TW; L.T = p->T; L.T_pad = p->T_pad; L.Cout_pad = p->Cout_pad;
     L.kstep = p->kstep;
+    L.k2_kernels = p->two_kernel ? 2 : 1;
     const uint64_t n2 = (uint64_t)n * n;
     L.blob_Wq_off = 0;
     L.blob_sW_off = align256(n2 * p->Cout_pad * Cin);
@@ -277,6 +278,36 @@ wq_status_t wq_contract_output(const wq_plan_t *plan, void *stream, void *worksp
                                size_t blob_bytes, float *y_dev) {
     return contract_impl(plan, stream, workspace_dev, workspace_bytes, weight_blob_dev, blob_bytes,
                          y_dev, nullptr);
+}
+
+static wq_status_t split_stage(const wq_plan_t *plan, void *stream, void *workspace_dev,
+                               size_t workspace_bytes, const void *weight_blob_dev,
+                               size_t blob_bytes, float *y_dev, int stages) {
+    if (!plan || ((stages & 2) && !y_dev)) return WQ_ERR_INVALID_ARG;
+    wq_status_t st = check_buffers(plan, weight_blob_dev, blob_bytes, workspace_dev, workspace_bytes);
+    if (st != WQ_OK) return st;
+    if (!plan->prepared.load()) return WQ_ERR_NOT_PREPARED;
+    char *ws = (char *)workspace_dev;
+    Blob bl = blob_of(plan, weight_blob_dev);
+    hipError_t e = wq_launch_contract_unfused(plan, (hipStream_t)stream,
+                                              (const int8_t *)(ws + plan->lay.ws_Xq_off),
+                                              (const float *)(ws + plan->lay.ws_sX_off), bl.Wq,
+                                              bl.sW, bl.bias, (float *)(ws + plan->lay.ws_M_off),
+                                              y_dev, stages);
+    return e == hipSuccess ? WQ_OK : WQ_ERR_DEVICE;
+}
+
+wq_status_t wq_contract(const wq_plan_t *plan, void *stream, void *workspace_dev,
+                        size_t workspace_bytes, const void *weight_blob_dev, size_t blob_bytes) {
+    return split_stage(plan, stream, workspace_dev, workspace_bytes, weight_blob_dev, blob_bytes,
+                       nullptr, 1);
+}
+
+wq_status_t wq_output_transform(const wq_plan_t *plan, void *stream, const void *workspace_dev,
+                                size_t workspace_bytes, const void *weight_blob_dev,
+                                size_t blob_bytes, float *y_dev) {
+    return split_stage(plan, stream, const_cast<void *>(workspace_dev), workspace_bytes,
+                       weight_blob_dev, blob_bytes, y_dev, 2);
 }
 
 wq_status_t wq_conv_forward(const wq_plan_t *plan, void *stream, const float *x_dev,

@@ -52,6 +52,7 @@ hipError_t wq_launch_input(const wq_plan *p, hipStream_t s, const float *x, int8
 hipError_t wq_launch_contract(const wq_plan *p, hipStream_t s, const int8_t *Xq, const float *sX,
                               const int8_t *Wq, const float *sW, const float *bias, float *Mbuf,
                               float *y, int32_t *P);
+// stages: bit 0 = tiled GEMM with group dequantization into Mbuf, bit 1 = output transform of Mbuf
 hipError_t wq_launch_contract_unfused(const wq_plan *p, hipStream_t s, const int8_t *Xq,
                                       const float *sX, const int8_t *Wq, const float *sW,
-                                      const float *bias, float *Mbuf, float *y);
+                                      const float *bias, float *Mbuf, float *y, int stages = 3);

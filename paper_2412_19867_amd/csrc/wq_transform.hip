@@ -218,11 +218,14 @@ __global__ __launch_bounds__(256) void k_input_transform(wq_xf xf, const float *
 #define WQ_BODY(I0)                                                                            \
     input_body<M, (I0), SPARSE>(xf, x, Xq, sX, H, W, Cin, TH, TW, T, T_pad, log2k, kstep_log2, \
                                 x_bytes, amax_s, r_s)
-    if (blockIdx.y == 0) {   // uniform: the first or the second half of the tap rows
-        WQ_BODY(0);
-    } else {
-        WQ_BODY(TR);
-    }
+    // uniform branch: which block of TR tap rows this workgroup forms
+    constexpr int NY = n / TR;
+    static_assert(NY * TR == n && NY <= 4, "unsupported tap-row split");
+    const int yb = blockIdx.y;
+    if (yb == 0) WQ_BODY(0);
+    if constexpr (NY > 1) { if (yb == 1) WQ_BODY(TR); }
+    if constexpr (NY > 2) { if (yb == 2) WQ_BODY(2 * TR); }
+    if constexpr (NY > 3) { if (yb == 3) WQ_BODY(3 * TR); }
 #undef WQ_BODY
 }
 
@@ -318,7 +321,8 @@ int ilog2(int v) {
 
 template <int M>
 hipError_t launch_input_m(const wq_plan *p, hipStream_t s, const float *x, int8_t *Xq, float *sX) {
-    const dim3 grid((unsigned)((p->T_pad / 16) * (p->Cin / 32)), 2), block(256);
+    const dim3 grid((unsigned)((p->T_pad / 16) * (p->Cin / 32)), (M + 2) / tap_rows_per_wg<M>()),
+        block(256);
     const int log2k = ilog2(p->g / 32), kstep_log2 = p->kstep == 32 ? 5 : 6;
     const unsigned x_bytes = (unsigned)((size_t)p->N * p->H * p->W * p->Cin * 4);
     if (p->sparse_bt)

@@ -20,14 +20,15 @@ STATUS_NAMES = {0: "WQ_OK", 1: "WQ_ERR_INVALID_ARG", 2: "WQ_ERR_UNSUPPORTED",
                 6: "WQ_ERR_DEVICE"}
 
 EXPORTS = ["wq_standard_transforms", "wq_plan_create", "wq_plan_destroy", "wq_plan_layout",
-           "wq_weight_prepare", "wq_input_transform", "wq_contract_output", "wq_conv_forward",
+           "wq_weight_prepare", "wq_input_transform", "wq_contract_output", "wq_contract",
+           "wq_output_transform", "wq_conv_forward",
            "wq_conv_forward_debug", "wq_status_string"]
 
 
 class Layout(ctypes.Structure):
     _fields_ = ([(k, ctypes.c_int32) for k in
                  ("N", "H", "W", "Cin", "Cout", "m", "n", "group_size", "groups",
-                  "TH", "TW", "T", "T_pad", "Cout_pad", "kstep")] +
+                  "TH", "TW", "T", "T_pad", "Cout_pad", "kstep", "k2_kernels")] +
                 [(k, ctypes.c_uint64) for k in
                  ("blob_bytes", "blob_Wq_off", "blob_sW_off", "blob_bias_off",
                   "ws_bytes", "ws_Xq_off", "ws_sX_off", "ws_M_off", "debug_P_bytes")])
@@ -58,6 +59,8 @@ def lib() -> ctypes.CDLL:
         L.wq_weight_prepare.argtypes = [vp, vp, vp, vp, vp, sz]
         L.wq_input_transform.argtypes = [vp, vp, vp, vp, sz]
         L.wq_contract_output.argtypes = [vp, vp, vp, sz, vp, sz, vp]
+        L.wq_contract.argtypes = [vp, vp, vp, sz, vp, sz]
+        L.wq_output_transform.argtypes = [vp, vp, vp, sz, vp, sz, vp]
         L.wq_conv_forward.argtypes = [vp, vp, vp, vp, sz, vp, sz, vp]
         L.wq_conv_forward_debug.argtypes = [vp, vp, vp, vp, sz, vp, sz, vp, vp, sz]
         L.wq_status_string.argtypes = [ip]
@@ -196,6 +199,16 @@ class Plan:
             .view(n2, L.T_pad // 16, L.groups, 16).permute(0, 1, 3, 2).reshape(n2, L.T_pad, L.groups)
         return Xq, sX
 
+    def product_view(self, ws):
+        """M [n*n][T][Cout] fp32: the dequantized Winograd-domain products wq_contract left
+        in the workspace (a strided view, no copy)."""
+        import torch
+        L = self.layout
+        n2 = L.n * L.n
+        M = ws[L.ws_M_off:L.ws_M_off + n2 * L.T_pad * L.Cout_pad * 4].view(torch.float32) \
+            .view(L.T_pad, n2, L.Cout_pad)
+        return M[:L.T, :, :L.Cout].permute(1, 0, 2)
+
     # ---- entry points ----
     def weight_prepare(self, w, bias, blob, stream=None):
         import torch
@@ -222,6 +235,22 @@ class Plan:
                                         _dev_ptr(blob, torch.uint8, "blob"), blob.numel(),
                                         _dev_ptr(y, torch.float32, "y", L.N * L.H * L.W * L.Cout)),
                "wq_contract_output")
+
+    def contract(self, ws, blob, stream=None):
+        import torch
+        _check(lib().wq_contract(self._h, _stream_handle(stream),
+                                 _dev_ptr(ws, torch.uint8, "workspace"), ws.numel(),
+                                 _dev_ptr(blob, torch.uint8, "blob"), blob.numel()),
+               "wq_contract")
+
+    def output_transform(self, ws, blob, y, stream=None):
+        import torch
+        L = self.layout
+        _check(lib().wq_output_transform(self._h, _stream_handle(stream),
+                                         _dev_ptr(ws, torch.uint8, "workspace"), ws.numel(),
+                                         _dev_ptr(blob, torch.uint8, "blob"), blob.numel(),
+                                         _dev_ptr(y, torch.float32, "y", L.N * L.H * L.W * L.Cout)),
+               "wq_output_transform")
 
     def forward(self, x, blob, ws, y, stream=None):
         import torch

@@ -51,9 +51,15 @@ def run_gpu(wq, d, mats, want_P=True):
         y_dbg.fill_(float("nan"))
         plan.forward_debug(x, blob, ws, y_dbg, P)
         torch.cuda.synchronize()
+    # stage 2 and stage 3 as separate calls (the two-kernel form, whatever the plan defaults to)
+    y_split = plan.alloc_output()
+    y_split.fill_(float("nan"))
+    plan.contract(ws, blob)
+    plan.output_transform(ws, blob, y_split)
+    torch.cuda.synchronize()
     Wq, sW, bias = plan.blob_views(blob)
     Xq, sX = plan.workspace_views(ws)
-    out = dict(Wq=Wq[:, :L.Cout].cpu().numpy(), sW=sW[:, :, :L.Cout].cpu().numpy(),
+    out = dict(M=plan.product_view(ws).cpu().numpy(), y_split=y_split.cpu().numpy(),Wq=Wq[:, :L.Cout].cpu().numpy(), sW=sW[:, :, :L.Cout].cpu().numpy(),
                Xq=Xq[:, :L.T].cpu().numpy(), sX=sX[:, :L.T].cpu().numpy(),
                y=y.cpu().numpy(), P=None if P is None else P.cpu().numpy(),
                y_dbg=None if y_dbg is None else y_dbg.cpu().numpy(),
@@ -82,7 +88,13 @@ def check(wq, d, want_P=True):
         assert np.array_equal(got["P"], ref["P"]), f"{lay.name}: int32 partial sums"
     scale = np.abs(ref["y64"]).max()
     worst = 0.0
-    for key in ("y", "y_dbg"):
+    m_scale = np.abs(ref["M"]).max()
+    m_err = np.abs(got["M"].astype(np.float64) - ref["M"]).max()
+    # absolute floor: where the fp32 product of the two scales is sub-normal it carries an
+    # error of up to one sub-normal step (2^-149), times |P| <= g*127^2, per group
+    m_tol = Y_TOL * m_scale + lay.Cin * 127.0 ** 2 * 2.0 ** -149
+    assert m_err <= m_tol, f"{lay.name}: M max|err| {m_err:.3e} > {m_tol:.3e}"
+    for key in ("y", "y_dbg", "y_split"):
         if got[key] is None:
             continue
         assert np.isfinite(got[key]).all(), f"{lay.name}: {key} has unwritten or non-finite entries"

@@ -10,8 +10,9 @@
 // the blocked operand layout (see include/wq.h).
 //   phase A  each lane transforms its two channels with fused-multiply-add
 //            chains (left factor first, inner index ascending, from +0) and
-//            reduces |value| over its row with four DPP steps per tap;
-//   phase B  one lane per (tap, group) combines the rows of the group, does
+//            reduces |value| over each 4-lane group with two DPP steps per tap
+//            (the four partial maxima of a row go to LDS);
+//   phase B  one lane per (tap, group) combines the partial maxima of the group, does
 //            the two correctly rounded divisions s = a/127, r = 127/a and
 //            stores s; r goes through LDS;
 //   phase C  every lane quantizes its values as rint(v*r) (rounded product,
@@ -38,16 +39,18 @@ __device__ __forceinline__ uint32_t dpp_max(uint32_t v) {
     return max(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xf, 0xf, true));
 }
 
-// max over the 16 lanes of a DPP row, result in every lane
-__device__ __forceinline__ uint32_t row_max16(uint32_t v) {
+// max over each aligned group of 4 lanes, result in all 4 lanes
+__device__ __forceinline__ uint32_t quad_max(uint32_t v) {
     v = dpp_max<0xB1>(v);   // quad_perm [1,0,3,2]
     v = dpp_max<0x4E>(v);   // quad_perm [2,3,0,1]
-    v = dpp_max<0x141>(v);  // row_half_mirror
-    v = dpp_max<0x140>(v);  // row_mirror
     return v;
 }
 
-__device__ __forceinline__ uint32_t abs_bits(float v) { return __float_as_uint(v) & 0x7fffffffu; }
+// bit pattern of max(|a|, |b|): one v_max_f32 with source modifiers.  The operands are
+// finite results of fused multiply-adds, so the float maximum orders them like their bits.
+__device__ __forceinline__ uint32_t abs_max_bits(float a, float b) {
+    return __float_as_uint(__builtin_fmaxf(__builtin_fabsf(a), __builtin_fabsf(b)));
+}
 
 // rint(v*r) as the low byte of a two's-complement code; |v*r| <= 127 + ulp.
 __device__ __forceinline__ uint32_t quant_code(float v, float r) {
@@ -69,12 +72,13 @@ __device__ __forceinline__ unsigned blocked_offset(int chunk, int row16, int l16
 }
 
 // Phases B and C for NT consecutive taps starting at tap t0.
-//   amax_s/r_s   LDS [NT][16]
+//   amax_s       LDS [NT][16 rows][4 quads]: partial maxima of the 4-lane groups of every row
+//   r_s          LDS [NT][16]
 //   log2k        log2(units per group); the workgroup holds 16>>log2k rows-of-groups
 //   code_rsrc    buffer over the int8 tensor; lane_off = the lane's byte offset inside a tap plane
 //   scale index  scale_base + t*scale_plane + item (item = row-of-group index inside the workgroup)
 template <int NT>
-__device__ __forceinline__ void quantize_and_store(const float2 (&vals)[NT], uint32_t (*amax_s)[16],
+__device__ __forceinline__ void quantize_and_store(const float2 (&vals)[NT], uint4 (*amax_s)[16],
                                                    float (*r_s)[16], int log2k, int t0,
                                                    __amdgpu_buffer_rsrc_t code_rsrc, unsigned lane_off,
                                                    unsigned plane_bytes, bool lane_ok,
@@ -86,7 +90,10 @@ __device__ __forceinline__ void quantize_and_store(const float2 (&vals)[NT], uin
     for (int it = tid; it < NT * ni; it += 256) {
         const int tl = it >> ni_log2, item = it & (ni - 1);
         uint32_t a = 0;
-        for (int q = 0; q < k; ++q) a = max(a, amax_s[tl][item * k + q]);
+        for (int q = 0; q < k; ++q) {
+            const uint4 v = amax_s[tl][item * k + q];
+            a = max(max(a, max(v.x, v.y)), max(v.z, v.w));
+        }
         const float af = __uint_as_float(a);
         float s = 0.0f, r = 0.0f;
         if (af >= 127.0f * FLT_MIN) {
@@ -119,7 +126,7 @@ __device__ __forceinline__ void input_body(const wq_xf &xf, const float *__restr
                                            int8_t *__restrict__ Xq, float *__restrict__ sX, int H,
                                            int W, int Cin, int TH, int TW, int T, int T_pad,
                                            int log2k, int kstep_log2, unsigned x_bytes,
-                                           uint32_t (*amax_s)[16], float (*r_s)[16]) {
+                                           uint4 (*amax_s)[16], float (*r_s)[16]) {
     constexpr int n = M + 2, TR = tap_rows_per_wg<M>(), NT = TR * n;
     using Pat = wq_pattern<M>;
     const int tid = threadIdx.x, row = tid >> 4, l16 = tid & 15;
@@ -186,11 +193,12 @@ __device__ __forceinline__ void input_body(const wq_xf &xf, const float *__restr
                     ay = __builtin_fmaf(Tm[r][kk].y, xf.BT[j * n + kk], ay);
                 }
             X[r * n + j] = make_float2(ax, ay);
-            am[j] = row_max16(max(abs_bits(ax), abs_bits(ay)));
+            am[j] = quad_max(abs_max_bits(ax, ay));
         }
-        if (l16 == 0) {
+        {   // all four lanes of a group store the same value to the same word
+            uint32_t *dst = reinterpret_cast<uint32_t *>(&amax_s[r * n][row]) + (l16 >> 2);
 #pragma unroll
-            for (int j = 0; j < n; ++j) amax_s[r * n + j][row] = am[j];
+            for (int j = 0; j < n; ++j) dst[j * 64] = am[j];   // 64 words per tap
         }
     }
     const int RB = T_pad >> 4;
@@ -213,7 +221,7 @@ __global__ __launch_bounds__(256) void k_input_transform(wq_xf xf, const float *
                                                          int log2k, int kstep_log2,
                                                          unsigned x_bytes) {
     constexpr int n = M + 2, TR = tap_rows_per_wg<M>();
-    __shared__ uint32_t amax_s[TR * n][16];
+    __shared__ uint4 amax_s[TR * n][16];
     __shared__ float r_s[TR * n][16];
 #define WQ_BODY(I0)                                                                            \
     input_body<M, (I0), SPARSE>(xf, x, Xq, sX, H, W, Cin, TH, TW, T, T_pad, log2k, kstep_log2, \
@@ -237,7 +245,7 @@ __global__ __launch_bounds__(256) void k_weight_transform(wq_xf xf, const float 
                                                           int Cout_pad, int log2k, int kstep_log2) {
     constexpr int n = M + 2, n2 = n * n;
     using Pat = wq_pattern<M>;
-    __shared__ uint32_t amax_s[n2][16];
+    __shared__ uint4 amax_s[n2][16];
     __shared__ float r_s[n2][16];
     const int tid = threadIdx.x, row = tid >> 4, l16 = tid & 15;
     const int k = 1 << log2k;
@@ -288,11 +296,12 @@ __global__ __launch_bounds__(256) void k_weight_transform(wq_xf xf, const float 
                         ay = __builtin_fmaf(U[i][kk].y, xf.G[j * 3 + kk], ay);
                     }
                 X[i * n + j] = make_float2(ax, ay);
-                am[j] = row_max16(max(abs_bits(ax), abs_bits(ay)));
+                am[j] = quad_max(abs_max_bits(ax, ay));
             }
-            if (l16 == 0) {
+            {   // all four lanes of a group store the same value to the same word
+                uint32_t *dst = reinterpret_cast<uint32_t *>(&amax_s[i * n][row]) + (l16 >> 2);
 #pragma unroll
-                for (int j = 0; j < n; ++j) amax_s[i * n + j][row] = am[j];
+                for (int j = 0; j < n; ++j) dst[j * 64] = am[j];   // 64 words per tap
             }
         }
     }

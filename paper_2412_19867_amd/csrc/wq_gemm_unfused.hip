@@ -9,12 +9,16 @@
 //                       256 threads copy four 16-row weight blocks and four
 //                       16-row activation blocks (already in MFMA operand
 //                       order) plus the 64+64 scales of the group into LDS,
-//                       double buffered; every wave owns a 32x32 quarter
+//                       double buffered, fed from a register ring that keeps four
+//                       K-steps in flight; every wave owns a 32x32 quarter
 //                       (2x2 int8 MFMA blocks, fresh int32 accumulators per
 //                       group) and dequantizes into fp32 at each group end.
 //   k_output_transform  one workgroup per (tile, 64 channels), one wave per output
 //                       column: y = A^T M A + bias through LDS, NHWC store with the
 //                       ragged edge masked.
+#include <cstdlib>
+#include <cstring>
+
 #include "wq_internal.h"
 
 namespace {
@@ -33,17 +37,24 @@ struct GArgs {
     int Cin, T_pad, Cout_pad, log2g, n2;
 };
 
-template <bool K64, bool CPG1, bool WIDE>
+// TBW = 16-tile blocks per workgroup (4: a 64x64 output tile, waves 2x2; 2: 32 tiles x 128
+// channels, waves 1x4, for layers whose padded tile count is an odd multiple of 32).
+template <bool K64, bool CPG1, bool WIDE, int TBW>
 __global__ __launch_bounds__(256, 2) void k_gemm_dequant(const GArgs a) {
     constexpr int KSTEP = K64 ? 64 : 32, KB = KSTEP / 4;
-    constexpr int BLK = 16 * KSTEP;           // bytes of one K-step of a 16-row block
-    constexpr int LPT = 8 * BLK / (256 * 16); // 16-byte loads per thread per K-step
-    __shared__ __attribute__((aligned(16))) char opnd[2][8 * BLK];   // blocks 0-3 weights, 4-7 activations
-    __shared__ __attribute__((aligned(16))) float sc[2][128];        // 64 weight scales, 64 activation scales
+    constexpr int BLK = 16 * KSTEP;              // bytes of one K-step of a 16-row block
+    constexpr int OBW = TBW == 4 ? 4 : 8;        // 16-channel weight blocks per workgroup
+    constexpr int NB = OBW + TBW;                // blocks per stage: weights first, then activations
+    constexpr int CPB = BLK / 16;                // 16-byte chunks per block
+    constexpr int LPT = (NB * CPB + 255) / 256;  // 16-byte loads per thread per K-step
+    constexpr int WN = OBW / 2, NSW = OBW * 16, NSX = TBW * 16;   // waves along channels; scales per stage
+    constexpr unsigned kInvalid = 1u << 31;      // an offset past the end of any buffer (all < 2 GiB): loads 0
+    __shared__ __attribute__((aligned(16))) char opnd[2][NB * BLK];
+    __shared__ __attribute__((aligned(16))) float sc[2][NSW + NSX];   // weight scales, then activation scales
 
     const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15, q = lane >> 4;
-    const int w = __builtin_amdgcn_readfirstlane(tid >> 6), wm = w >> 1, wn = w & 1;
-    const int t = blockIdx.z, ob0 = blockIdx.x * 4, tb0 = blockIdx.y * 4;   // in 16-row blocks
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6), wm = w / WN, wn = w % WN;
+    const int t = blockIdx.z, ob0 = blockIdx.x * OBW, tb0 = blockIdx.y * TBW;   // in 16-row blocks
     const int Cin = a.Cin, T_pad = a.T_pad, Cout_pad = a.Cout_pad;
     const int groups = Cin >> a.log2g, cps = Cin / KSTEP;
     const int cpg_mask = ((1 << a.log2g) / KSTEP) - 1;
@@ -58,45 +69,57 @@ __global__ __launch_bounds__(256, 2) void k_gemm_dequant(const GArgs a) {
     const __amdgpu_buffer_rsrc_t rSX = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<float *>(a.sX), 0, (int)(n2 * (unsigned)T_pad * (unsigned)groups * 4u), kBufFlags);
 
-    // which 16 bytes of the 8-block stage this thread copies (per load u), as buffer offsets
-    int vop[LPT];
+    // which 16 bytes of the stage this thread copies with load u, as buffer offsets; a wave's
+    // 64 chunks lie in one block (K-step 64) or two (K-step 32), all weights or all activations
+    unsigned vop[LPT];
+    bool is_w[LPT];
 #pragma unroll
     for (int u = 0; u < LPT; ++u) {
-        const int c = tid + u * 256, blk = c / (BLK / 16), off = (c % (BLK / 16)) * 16;
-        vop[u] = (blk < 4 ? (ob0 + blk) : (tb0 + blk - 4)) * 16 * Cin + off;
+        const int c = tid + u * 256, blk = c / CPB, off = (c % CPB) * 16;
+        is_w[u] = (w * 64 + u * 256) / CPB < OBW;   // wave-uniform
+        const int row = blk < OBW ? ob0 + blk : tb0 + blk - OBW;
+        const bool ok = blk < NB && row * 16 < (blk < OBW ? Cout_pad : T_pad);
+        vop[u] = ok ? (unsigned)(row * 16 * Cin + off) : kInvalid;
     }
-    // scales: wave 0 copies the 64 weight scales, wave 1 the 64 activation scales of the group
-    const int vsc = w == 0 ? (ob0 * 16 + lane) * 4
-                           : ((tb0 + (lane >> 4)) * groups * 64 + (lane & 15) * 4);
+    // scales of a group: threads 0..NSW-1 the weight scales, the next NSX the activation scales
+    const bool sc_w = w * 64 < NSW;                 // wave-uniform
+    unsigned vsc = kInvalid;
+    if (tid < NSW) {
+        if (ob0 * 16 + tid < Cout_pad) vsc = (unsigned)(ob0 * 16 + tid) * 4u;
+    } else if (tid < NSW + NSX) {
+        const int r = tid - NSW;                    // tile inside the workgroup's tile range
+        if ((tb0 + (r >> 4)) * 16 < T_pad)
+            vsc = (unsigned)((tb0 + (r >> 4)) * groups * 64 + (r & 15) * 4);
+    }
     const unsigned baseW = (unsigned)t * Cout_pad * Cin, baseX = (unsigned)t * T_pad * Cin;
     const unsigned baseSW = (unsigned)t * groups * Cout_pad * 4, baseSX = (unsigned)t * T_pad * groups * 4;
 
-    // K-step s+1 is fetched into registers while step s is consumed from LDS buffer s & 1,
-    // then moved to the other buffer.  (Deeper register rings were measured: no gain.)
-    v4i pre[LPT];
-    float psc;
+    // A K-step costs one trip to memory (about a microsecond) unless it was requested long
+    // before: PD K-steps are in flight in a register ring whose slots are compile-time
+    // indices (the main loop is unrolled PD times), step s is consumed from LDS buffer
+    // s & 1 while step s+1 moves from its ring slot into the other buffer.  Every wave
+    // issues the same number of loads per K-step and no load sits under a branch, so the
+    // wait before the move leaves the newer K-steps outstanding.
+    constexpr int PD = 4;
+    v4i pre[PD][LPT];
+    float psc[PD];
     auto fetch = [&](int s, v4i (&dst)[LPT], float &dsc) {   // global -> registers for K-step s
 #pragma unroll
         for (int u = 0; u < LPT; ++u) {
-            // K32: threads 0-127 (waves 0,1) copy weights; K64: load 0 copies weights, load 1 activations
-            const bool isW = K64 ? (u == 0) : (w < 2);
-            dst[u] = isW ? __builtin_amdgcn_raw_buffer_load_b128(rW, vop[u], baseW + (unsigned)s * BLK, 0)
-                         : __builtin_amdgcn_raw_buffer_load_b128(rX, vop[u], baseX + (unsigned)s * BLK, 0);
+            const unsigned so = (is_w[u] ? baseW : baseX) + (unsigned)s * BLK;
+            dst[u] = __builtin_amdgcn_raw_buffer_load_b128(is_w[u] ? rW : rX, vop[u], so, 0);
         }
         const unsigned gam = (unsigned)(s * KSTEP) >> a.log2g;
-        dsc = 0.f;
-        if (w == 0)
-            dsc = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
-                                                rSW, vsc, baseSW + gam * (unsigned)Cout_pad * 4u, 0));
-        else if (w == 1)
-            dsc = __builtin_bit_cast(float,
-                                     __builtin_amdgcn_raw_buffer_load_b32(rSX, vsc, baseSX + gam * 64u, 0));
+        dsc = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
+                                            sc_w ? rSW : rSX, vsc,
+                                            sc_w ? baseSW + gam * (unsigned)Cout_pad * 4u : baseSX + gam * 64u, 0));
     };
     auto commit = [&](int buf, const v4i (&src)[LPT], float ssc) {   // registers -> LDS
 #pragma unroll
         for (int u = 0; u < LPT; ++u)
-            *reinterpret_cast<v4i *>(&opnd[buf][(tid + u * 256) * 16]) = src[u];
-        if (w < 2) sc[buf][w * 64 + lane] = ssc;
+            if ((u + 1) * 256 <= NB * CPB || tid + u * 256 < NB * CPB)
+                *reinterpret_cast<v4i *>(&opnd[buf][(tid + u * 256) * 16]) = src[u];
+        if (tid < NSW + NSX) sc[buf][tid] = ssc;
     };
 
     v4i acc[2][2];
@@ -113,18 +136,24 @@ __global__ __launch_bounds__(256, 2) void k_gemm_dequant(const GArgs a) {
         }
     int in_chunk = 0;
 
-    fetch(0, pre, psc);
-    commit(0, pre, psc);
+    const int last = cps - 1;
+#pragma unroll
+    for (int u = 0; u < PD; ++u) fetch(min(u, last), pre[u], psc[u]);
+    commit(0, pre[0], psc[0]);
     __syncthreads();
-    for (int s = 0; s < cps; ++s) {
-        const int buf = s & 1;
-        if (s + 1 < cps) fetch(s + 1, pre, psc);
+    for (int s0 = 0; s0 < cps; s0 += PD) {
+#pragma unroll
+      for (int u = 0; u < PD; ++u) {
+        const int s = s0 + u;
+        if (s >= cps) break;
+        const int buf = u & 1;   // PD is even, so s & 1 == u & 1
+        fetch(min(s + PD, last), pre[u], psc[u]);   // slot u held step s, already in LDS
         // operands of this wave's 2x2 blocks
         v4i av[2], bv[2];
 #pragma unroll
         for (int e = 0; e < 2; ++e) {
             const char *pa = &opnd[buf][(2 * wn + e) * BLK + lane * KB];
-            const char *pb = &opnd[buf][(4 + 2 * wm + e) * BLK + lane * KB];
+            const char *pb = &opnd[buf][(OBW + 2 * wm + e) * BLK + lane * KB];
             if constexpr (K64) {
                 av[e] = *reinterpret_cast<const v4i *>(pa);
                 bv[e] = *reinterpret_cast<const v4i *>(pb);
@@ -153,7 +182,7 @@ __global__ __launch_bounds__(256, 2) void k_gemm_dequant(const GArgs a) {
                 const v4f sw = *reinterpret_cast<const v4f *>(&sc[buf][(2 * wn + no) * 16 + 4 * q]);
 #pragma unroll
                 for (int nt = 0; nt < 2; ++nt) {
-                    const float sx = sc[buf][64 + (2 * wm + nt) * 16 + l16];
+                    const float sx = sc[buf][NSW + (2 * wm + nt) * 16 + l16];
                     Mc[no][nt].x = __builtin_fmaf((float)acc[no][nt][0], sw.x * sx, Mc[no][nt].x);
                     Mc[no][nt].y = __builtin_fmaf((float)acc[no][nt][1], sw.y * sx, Mc[no][nt].y);
                     Mc[no][nt].z = __builtin_fmaf((float)acc[no][nt][2], sw.z * sx, Mc[no][nt].z);
@@ -175,8 +204,9 @@ __global__ __launch_bounds__(256, 2) void k_gemm_dequant(const GArgs a) {
                     }
             }
         }
-        if (s + 1 < cps) commit(buf ^ 1, pre, psc);
+        if (s + 1 < cps) commit(buf ^ 1, pre[(u + 1) % PD], psc[(u + 1) % PD]);
         __syncthreads();
+      }
     }
     // store M [tile][tap][Cout_pad] (a tile's taps together: the output transform reads them
     // from one contiguous region); the lane holds channels 4q..4q+3 of tile l16 in each block
@@ -252,11 +282,21 @@ __global__ __launch_bounds__(64 * M) void k_output_transform(const OArgs a) {
 }
 
 template <bool K64, bool CPG1>
-void launch_gemm(const GArgs &g, dim3 grid, hipStream_t s, bool wide) {
-    if (wide)
-        hipLaunchKernelGGL((k_gemm_dequant<K64, CPG1, true>), grid, dim3(256), 0, s, g);
-    else
-        hipLaunchKernelGGL((k_gemm_dequant<K64, CPG1, false>), grid, dim3(256), 0, s, g);
+void launch_gemm(const GArgs &g, hipStream_t s, bool wide, bool narrow) {
+    const unsigned taps = (unsigned)g.n2;
+    if (narrow) {
+        const dim3 grid((g.Cout_pad + 127) / 128, g.T_pad / 32, taps);
+        if (wide)
+            hipLaunchKernelGGL((k_gemm_dequant<K64, CPG1, true, 2>), grid, dim3(256), 0, s, g);
+        else
+            hipLaunchKernelGGL((k_gemm_dequant<K64, CPG1, false, 2>), grid, dim3(256), 0, s, g);
+    } else {
+        const dim3 grid((g.Cout_pad + 63) / 64, (g.T_pad + 63) / 64, taps);
+        if (wide)
+            hipLaunchKernelGGL((k_gemm_dequant<K64, CPG1, true, 4>), grid, dim3(256), 0, s, g);
+        else
+            hipLaunchKernelGGL((k_gemm_dequant<K64, CPG1, false, 4>), grid, dim3(256), 0, s, g);
+    }
 }
 
 template <int M>
@@ -278,11 +318,16 @@ hipError_t wq_launch_contract_unfused(const wq_plan *p, hipStream_t s, const int
     g.Cin = p->Cin; g.T_pad = p->T_pad; g.Cout_pad = p->Cout_pad; g.n2 = p->n * p->n;
     g.log2g = 0;
     while ((1 << g.log2g) < p->g) ++g.log2g;
-    const dim3 grid((p->Cout_pad + 63) / 64, (p->T_pad + 63) / 64, p->n * p->n);
     const bool k64 = p->kstep == 64, cpg1 = p->g == p->kstep, wide = p->groups > 8;
-    if (!k64) launch_gemm<false, true>(g, grid, s, wide);
-    else if (cpg1) launch_gemm<true, true>(g, grid, s, wide);
-    else launch_gemm<true, false>(g, grid, s, wide);
+    // 32-tile workgroups when the 64-tile ones would leave half a tile row of blocks empty
+    bool narrow = (p->T_pad % 64) == 32 && p->T_pad <= 160;
+    if (const char *e = std::getenv("WQ_GEMM_TILE")) {
+        if (!std::strcmp(e, "32")) narrow = true;
+        if (!std::strcmp(e, "64")) narrow = false;
+    }
+    if (!k64) launch_gemm<false, true>(g, s, wide, narrow);
+    else if (cpg1) launch_gemm<true, true>(g, s, wide, narrow);
+    else launch_gemm<true, false>(g, s, wide, narrow);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     }

@@ -16,7 +16,8 @@
 //            the two correctly rounded divisions s = a/127, r = 127/a and
 //            stores s; r goes through LDS;
 //   phase C  every lane quantizes its values as rint(v*r) (rounded product,
-//            then round-half-even via the 1.5*2^23 add) and stores two codes.
+//            then round-half-even via the 1.5*2^23 add); the codes go through LDS
+//            and leave as 16-byte stores that fill whole cache lines.
 // The input kernel additionally splits the n tap rows in two halves over
 // blockIdx.y: B^T d only has to be formed for the workgroup's rows, so the
 // split costs nothing but re-reading the tile through L1, and it halves the
@@ -30,8 +31,12 @@
 namespace {
 
 typedef int v2i __attribute__((ext_vector_type(2)));
+typedef int v4i __attribute__((ext_vector_type(4)));
 constexpr int kBufFlags = 0x00020000;   // raw buffer, 32-bit elements (gfx9 family)
 constexpr unsigned kInvalid = 1u << 30;  // added to an offset to push it past the buffer end
+// cache policy sc0 sc1 of a store: the data is written through to memory while the kernel runs
+// instead of being flushed from the XCD's L2 when it ends (measured: 5-8 % of the input kernel)
+constexpr int kWriteThrough = 17;
 
 template <int CTRL>
 __device__ __forceinline__ uint32_t dpp_max(uint32_t v) {
@@ -71,17 +76,55 @@ __device__ __forceinline__ unsigned blocked_offset(int chunk, int row16, int l16
             (unsigned)row16) * 16u + (unsigned)((2 * l16) & 15);
 }
 
+// Where a lane's two codes, and a thread's 16-byte piece, sit in the LDS staging area of one tap
+// and in global memory.  The 256 lanes of a workgroup produce 512 code bytes per tap = 32 pieces
+// of 16 bytes, each contiguous in the blocked layout:
+//   K-step 32 (group 32): the workgroup's 512 bytes are one whole 16-row block; a piece is
+//                         (K-quarter q, row pair); LDS pads 32 bytes per q against bank conflicts;
+//   K-step 64:            a piece is (DPP row, half of its 16 lanes).
+struct CodePlace {
+    unsigned lane_pos;    // LDS byte position of the lane's two codes inside a tap
+    unsigned piece_pos;   // LDS byte position of the thread's 16-byte piece inside a tap
+    unsigned piece_off;   // global byte offset of that piece inside a tap plane
+};
+constexpr int kTapStride = 640;   // LDS bytes per tap (512 + padding)
+
+// unit_of(r) gives (chunk, row16) of DPP row r; base = byte offset of the 16-row block row
+template <typename UnitOf>
+__device__ __forceinline__ CodePlace code_place(int tid, int kstep_log2, unsigned base, UnitOf unit_of) {
+    const int row = tid >> 4, l16 = tid & 15, p = tid & 31;
+    CodePlace c;
+    if (kstep_log2 == 5) {
+        int chunk, row16;
+        unit_of(row, chunk, row16);            // groups of 32: one unit per row, row16 == row
+        const int q = l16 >> 2;
+        c.lane_pos = (unsigned)((q * 8 + (row16 >> 1)) * 16 + q * 32 + (row16 & 1) * 8 + ((2 * l16) & 7));
+        c.piece_pos = (unsigned)(p * 16 + (p >> 3) * 32);
+        c.piece_off = base + blocked_offset(chunk, 2 * (p & 7), 4 * (p >> 3), 5);
+    } else {
+        c.lane_pos = (unsigned)((row * 2 + (l16 >> 3)) * 16 + ((2 * l16) & 15));
+        c.piece_pos = (unsigned)(p * 16);
+        int chunk, row16;
+        unit_of(p >> 1, chunk, row16);
+        c.piece_off = base + blocked_offset(chunk, row16, 8 * (p & 1), 6);
+    }
+    return c;
+}
+
 // Phases B and C for NT consecutive taps starting at tap t0.
 //   amax_s       LDS [NT][16 rows][4 quads]: partial maxima of the 4-lane groups of every row
 //   r_s          LDS [NT][16]
+//   codes_s      LDS [NT][kTapStride]: the workgroup's codes, staged so that they leave in
+//                16-byte pieces that fill whole 128-byte lines (2-byte stores straight from the
+//                lanes cost the input kernel a quarter of its time)
 //   log2k        log2(units per group); the workgroup holds 16>>log2k rows-of-groups
-//   code_rsrc    buffer over the int8 tensor; lane_off = the lane's byte offset inside a tap plane
+//   code_rsrc    buffer over the int8 tensor
 //   scale index  scale_base + t*scale_plane + item (item = row-of-group index inside the workgroup)
 template <int NT>
 __device__ __forceinline__ void quantize_and_store(const float2 (&vals)[NT], uint4 (*amax_s)[16],
-                                                   float (*r_s)[16], int log2k, int t0,
-                                                   __amdgpu_buffer_rsrc_t code_rsrc, unsigned lane_off,
-                                                   unsigned plane_bytes, bool lane_ok,
+                                                   float (*r_s)[16], char *codes_s, int log2k, int t0,
+                                                   __amdgpu_buffer_rsrc_t code_rsrc, CodePlace place,
+                                                   unsigned plane_bytes,
                                                    float *__restrict__ scales, long scale_base,
                                                    long scale_plane, int items_ok) {
     const int tid = threadIdx.x, row = tid >> 4;
@@ -104,15 +147,22 @@ __device__ __forceinline__ void quantize_and_store(const float2 (&vals)[NT], uin
         if (item < items_ok) scales[scale_base + (long)(t0 + tl) * scale_plane + item] = s;
     }
     __syncthreads();
-    if (lane_ok) {
+    {
         const int item = row >> log2k;
 #pragma unroll
         for (int tl = 0; tl < NT; ++tl) {
             const float r = r_s[tl][item];
             const uint32_t c = quant_code(vals[tl].x, r) | (quant_code(vals[tl].y, r) << 8);
-            __builtin_amdgcn_raw_buffer_store_b16((short)c, code_rsrc, lane_off,
-                                                  (unsigned)(t0 + tl) * plane_bytes, 0);
+            *reinterpret_cast<uint16_t *>(codes_s + tl * kTapStride + place.lane_pos) = (uint16_t)c;
         }
+    }
+    __syncthreads();
+    // 32 pieces per tap: thread tid moves piece tid % 32 of taps tid / 32, tid / 32 + 8, ...
+#pragma unroll
+    for (int tl = tid >> 5; tl < NT; tl += 8) {
+        const v4i v = *reinterpret_cast<const v4i *>(codes_s + tl * kTapStride + place.piece_pos);
+        __builtin_amdgcn_raw_buffer_store_b128(v, code_rsrc, place.piece_off,
+                                               (unsigned)(t0 + tl) * plane_bytes, kWriteThrough);
     }
 }
 
@@ -126,7 +176,7 @@ __device__ __forceinline__ void input_body(const wq_xf &xf, const float *__restr
                                            int8_t *__restrict__ Xq, float *__restrict__ sX, int H,
                                            int W, int Cin, int TH, int TW, int T, int T_pad,
                                            int log2k, int kstep_log2, unsigned x_bytes,
-                                           uint4 (*amax_s)[16], float (*r_s)[16]) {
+                                           uint4 (*amax_s)[16], float (*r_s)[16], char *codes_s) {
     constexpr int n = M + 2, TR = tap_rows_per_wg<M>(), NT = TR * n;
     using Pat = wq_pattern<M>;
     const int tid = threadIdx.x, row = tid >> 4, l16 = tid & 15;
@@ -204,12 +254,15 @@ __device__ __forceinline__ void input_body(const wq_xf &xf, const float *__restr
     const int RB = T_pad >> 4;
     const __amdgpu_buffer_rsrc_t rq = __builtin_amdgcn_make_buffer_rsrc(
         Xq, 0, (int)((unsigned)(n * n) * (unsigned)T_pad * (unsigned)Cin), kBufFlags);
-    const unsigned lane_off =
-        (unsigned)rb * 16u * (unsigned)Cin + blocked_offset(chunk, row16, l16, kstep_log2);
+    const CodePlace place =
+        code_place(tid, kstep_log2, (unsigned)rb * 16u * (unsigned)Cin, [&](int r, int &c, int &r16) {
+            c = gam * k + (r & (k - 1));
+            r16 = sub * (16 >> log2k) + (r >> log2k);
+        });
     // sX [t][rb][group][16]: this workgroup owns 16/k consecutive entries per tap
     const long scale_base = ((long)rb * groups + gam) * 16 + sub * (16 >> log2k);
-    quantize_and_store<NT>(X, amax_s, r_s, log2k, I0 * n, rq, lane_off,
-                           (unsigned)T_pad * (unsigned)Cin, true, sX, scale_base,
+    quantize_and_store<NT>(X, amax_s, r_s, codes_s, log2k, I0 * n, rq, place,
+                           (unsigned)T_pad * (unsigned)Cin, sX, scale_base,
                            (long)RB * groups * 16, 16);
 }
 
@@ -223,9 +276,10 @@ __global__ __launch_bounds__(256) void k_input_transform(wq_xf xf, const float *
     constexpr int n = M + 2, TR = tap_rows_per_wg<M>();
     __shared__ uint4 amax_s[TR * n][16];
     __shared__ float r_s[TR * n][16];
+    __shared__ __attribute__((aligned(16))) char codes_s[TR * n * kTapStride];
 #define WQ_BODY(I0)                                                                            \
     input_body<M, (I0), SPARSE>(xf, x, Xq, sX, H, W, Cin, TH, TW, T, T_pad, log2k, kstep_log2, \
-                                x_bytes, amax_s, r_s)
+                                x_bytes, amax_s, r_s, codes_s)
     // uniform branch: which block of TR tap rows this workgroup forms
     constexpr int NY = n / TR;
     static_assert(NY * TR == n && NY <= 4, "unsupported tap-row split");
@@ -247,6 +301,7 @@ __global__ __launch_bounds__(256) void k_weight_transform(wq_xf xf, const float 
     using Pat = wq_pattern<M>;
     __shared__ uint4 amax_s[n2][16];
     __shared__ float r_s[n2][16];
+    __shared__ __attribute__((aligned(16))) char codes_s[n2 * kTapStride];
     const int tid = threadIdx.x, row = tid >> 4, l16 = tid & 15;
     const int k = 1 << log2k;
     const int CC = Cin >> 5, groups = CC >> log2k;
@@ -307,12 +362,15 @@ __global__ __launch_bounds__(256) void k_weight_transform(wq_xf xf, const float 
     }
     const __amdgpu_buffer_rsrc_t rq = __builtin_amdgcn_make_buffer_rsrc(
         Wq, 0, (int)((unsigned)n2 * (unsigned)Cout_pad * (unsigned)Cin), kBufFlags);
-    const unsigned lane_off =
-        (unsigned)rb * 16u * (unsigned)Cin + blocked_offset(chunk, row16, l16, kstep_log2);
+    const CodePlace place =
+        code_place(tid, kstep_log2, (unsigned)rb * 16u * (unsigned)Cin, [&](int r, int &c, int &r16) {
+            c = gam * k + (r & (k - 1));
+            r16 = sub * (16 >> log2k) + (r >> log2k);
+        });
     // sW [t][group][Cout_pad]: this workgroup owns 16/k consecutive output channels
     const long scale_base = (long)gam * Cout_pad + rb * 16 + sub * (16 >> log2k);
-    quantize_and_store<n2>(X, amax_s, r_s, log2k, 0, rq, lane_off,
-                           (unsigned)Cout_pad * (unsigned)Cin, true, sW, scale_base,
+    quantize_and_store<n2>(X, amax_s, r_s, codes_s, log2k, 0, rq, place,
+                           (unsigned)Cout_pad * (unsigned)Cin, sW, scale_base,
                            (long)groups * Cout_pad, 16);
 }
 

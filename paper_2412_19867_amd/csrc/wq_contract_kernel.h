@@ -68,7 +68,8 @@ __global__ __launch_bounds__(64 * (M + 2) * KS) void k_contract_output(const Arg
     constexpr int KSTEP = K64 ? 64 : 32;   // K per MFMA
     constexpr int KB = KSTEP / 4;          // operand bytes per lane per MFMA
     constexpr int NW = n * KS;             // waves
-    constexpr int BP = M == 6 ? 3 : 2;     // output columns per LDS pass
+    // output columns per LDS pass: all M when the exchange area fits 64 KiB, else half of them
+    constexpr int BP = NW * M * 16 * RS_STRIDE * 4 <= 65536 ? M : M / 2;
     constexpr int NTH = (64 * NW / 256) * 256;   // threads of the final phase: a multiple of 256,
                                                  // so that a thread keeps its (tile, channel) position
     using Pat = wq_pattern<M>;

@@ -345,19 +345,14 @@ __global__ __launch_bounds__(64 * (M + 2) * KS) void k_contract_output(const Arg
                 for (int idx = tid < NTH ? tid : BP * 256; idx < BP * 256; idx += NTH) {
                     const int bp = idx >> 8;   // idx & 255 == tid & 255 for every iteration
                     const int bcol = p * BP + bp;
-                    float Yv[M];
-#pragma unroll
-                    for (int aa = 0; aa < M; ++aa) Yv[aa] = 0.f;
+                    float Yv[M], rv[n];
 #pragma unroll
                     for (int ii = 0; ii < n; ++ii) {
-                        float rv = Rs[ii][bp][tl * RS_STRIDE + ol];
+                        rv[ii] = Rs[ii][bp][tl * RS_STRIDE + ol];
 #pragma unroll
-                        for (int k2 = 1; k2 < KS; ++k2) rv += Rs[k2 * n + ii][bp][tl * RS_STRIDE + ol];
-#pragma unroll
-                        for (int aa = 0; aa < M; ++aa)
-                            if (!ATSP || Pat::at(aa, ii))
-                                Yv[aa] = __builtin_fmaf(a.xf.AT[aa * n + ii], rv, Yv[aa]);
+                        for (int k2 = 1; k2 < KS; ++k2) rv[ii] += Rs[k2 * n + ii][bp][tl * RS_STRIDE + ol];
                     }
+                    wq_apply_at<M, ATSP>(a.xf, rv, Yv);
                     const int hv = out_lim[nt] & 0xff, wv = out_lim[nt] >> 8;
                     const int o = o0 + no * 16 + ol;
                     if (bcol < wv && o < a.Cout) {

@@ -262,6 +262,7 @@ __global__ __launch_bounds__(64 * M) void k_output_transform(const OArgs a) {
         *reinterpret_cast<float4 *>(&Ms[t][c4]) = v;
     }
     __syncthreads();
+    // column pass R = M A^T[b][:] with the wave's (run-time) row b of A^T
     float atb[n];
 #pragma unroll
     for (int j = 0; j < n; ++j) atb[j] = a.xf.AT[b * n + j];
@@ -279,12 +280,11 @@ __global__ __launch_bounds__(64 * M) void k_output_transform(const OArgs a) {
     if (o < a.Cout && b < wv) {
         const float bv = a.bias[o];
         float *dst = a.y + ((size_t)(bb * a.H + th * M) * a.W + tw * M + b) * a.Cout + o;
+        float Yv[M];
+        wq_apply_at<M, ATSP>(a.xf, R, Yv);
 #pragma unroll
         for (int aa = 0; aa < M; ++aa) {
-            float yv = 0.f;
-#pragma unroll
-            for (int i = 0; i < n; ++i)
-                if (!ATSP || Pat::at(aa, i)) yv = __builtin_fmaf(a.xf.AT[aa * n + i], R[i], yv);
+            const float yv = Yv[aa];
             if (aa < hv)   // streaming store: y is not read again by this layer
                 __builtin_nontemporal_store(yv + bv, &dst[(size_t)aa * a.W * a.Cout]);
         }

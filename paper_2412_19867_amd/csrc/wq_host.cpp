@@ -70,6 +70,23 @@ void detect_patterns(wq_plan *p) {
     for (int a = 0; a < M; ++a)
         for (int i = 0; i < n; ++i)
             if (!wq_pattern<M>::at(a, i) && p->xf.AT[a * n + i] != 0.0f) p->sparse_at = false;
+    // paired columns: AT[a][2k] = (-1)^a r_k AT[a][2k-1] within a few fp32 roundings (the entries
+    // of a rescaled matrix were rounded one by one)
+    for (int k = 1; k <= (n - 2) / 2 && p->sparse_at; ++k) {
+        const int i1 = 2 * k - 1, i2 = 2 * k;
+        int best = 0;
+        for (int a = 1; a < M; ++a)
+            if (std::fabs(p->xf.AT[a * n + i1]) > std::fabs(p->xf.AT[best * n + i1])) best = a;
+        const double d = p->xf.AT[best * n + i1];
+        if (d == 0.0) { p->sparse_at = false; break; }
+        const double r = ((best & 1) ? -1.0 : 1.0) * (double)p->xf.AT[best * n + i2] / d;
+        for (int a = 0; a < M; ++a) {
+            const double want = ((a & 1) ? -1.0 : 1.0) * r * (double)p->xf.AT[a * n + i1];
+            const double got = p->xf.AT[a * n + i2];
+            if (std::fabs(got - want) > 4.0 * 5.97e-8 * std::fabs(got) + 1e-37) p->sparse_at = false;
+        }
+        p->xf.ATr[k - 1] = (float)r;
+    }
 }
 
 // 1-D minimal-filtering identity: the triple computes y[a] = sum_k d[a+k] g[k].

@@ -14,6 +14,10 @@ struct wq_xf {
     float BT[64];  // n x n, row-major, row stride n
     float G[24];   // n x 3
     float AT[48];  // m x n, row stride n
+    // When A^T has the paired form (columns 2k-1 and 2k belong to points p and -p, up to a
+    // column scale): AT[a][2k] = (-1)^a * ATr[k-1] * AT[a][2k-1].  Then a column pair costs
+    // E = v1 + r v2, O = v1 - r v2 and one multiply-add per output row instead of two.
+    float ATr[4];
 };
 
 struct wq_plan {
@@ -24,6 +28,8 @@ struct wq_plan {
     // true when the zero entries of the standard matrices are also zero here
     // (always the case for diagonal rescalings of the standard matrices), so
     // that kernels may skip those terms of the fused-multiply-add chains.
+    // sparse_at additionally requires the paired form of A^T (see wq_xf::ATr); matrices
+    // without it take the dense output-transform code.
     bool sparse_bt, sparse_g, sparse_at;
     // stages 2+3 as GEMM + separate output transform (few tiles, many channels) instead of fused
     bool two_kernel;
@@ -43,6 +49,33 @@ struct wq_pattern {
     static constexpr bool g(int i, int k) { return i == 0 ? k == 0 : (i == n - 1 ? k == 2 : true); }
     static constexpr bool at(int a, int i) { return i == 0 ? a == 0 : (i == n - 1 ? a == M - 1 : true); }
 };
+
+// out[a] = sum_i A^T[a][i] * v[i].  PAIRED: the standard zero pattern and the paired form of
+// A^T (wq_xf::ATr) are known to hold: 26 instead of 48 multiply-adds for F(6,3).
+template <int M, bool PAIRED>
+__device__ __forceinline__ void wq_apply_at(const wq_xf &xf, const float (&v)[M + 2], float (&out)[M]) {
+    constexpr int n = M + 2;
+#pragma unroll
+    for (int a = 0; a < M; ++a) out[a] = 0.f;
+    if constexpr (!PAIRED) {
+#pragma unroll
+        for (int i = 0; i < n; ++i)
+#pragma unroll
+            for (int a = 0; a < M; ++a) out[a] = __builtin_fmaf(xf.AT[a * n + i], v[i], out[a]);
+    } else {
+        out[0] = xf.AT[0] * v[0];
+#pragma unroll
+        for (int k = 1; k <= (n - 2) / 2; ++k) {
+            const float r = xf.ATr[k - 1];
+            const float E = __builtin_fmaf(r, v[2 * k], v[2 * k - 1]);
+            const float O = __builtin_fmaf(-r, v[2 * k], v[2 * k - 1]);
+#pragma unroll
+            for (int a = 0; a < M; ++a)
+                out[a] = __builtin_fmaf(xf.AT[a * n + 2 * k - 1], (a & 1) ? O : E, out[a]);
+        }
+        out[M - 1] = __builtin_fmaf(xf.AT[(M - 1) * n + n - 1], v[n - 1], out[M - 1]);
+    }
+}
 
 // Kernel launchers (each enqueues on `s` and returns the launch status).
 hipError_t wq_launch_weight(const wq_plan *p, hipStream_t s, const float *w, const float *bias,

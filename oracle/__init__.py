@@ -164,3 +164,49 @@ def qwino_pipeline(x, w, bias, AT, BT, G, m: int, g: int, want_P: bool = False) 
     M, P = res if want_P else (res, None)
     y64, y32 = output_transform(M, AT, bias, N, H, W, m)
     return dict(Xq=Xq, sX=sX, Wq=Wq, sW=sW, P=P, M=M, y64=y64, y=y32)
+
+
+# ---- the group-wise quantized standard (direct) convolution: the paper's runtime comparison point
+def quantize_pixels(x, g: int):
+    """x [N][H][W][Cin] fp32 -> (xq [N*H*W][Cin] int8, sx [N*H*W][Cin/g] fp32)."""
+    x = _f32(x)
+    Cin = x.shape[-1]
+    P = x.size // Cin
+    xq = np.empty((P, Cin), dtype=np.int8)
+    sx = np.empty((P, Cin // g), dtype=np.float32)
+    _load().oracle_quantize_pixels(_p(x), ctypes.c_long(P), Cin, g, _p(xq), _p(sx))
+    return xq, sx
+
+
+def quantize_filters(w, g: int):
+    """w [Cout][Cin][3][3] fp32 -> (wq [9][Cout][Cin] int8, sw [9][Cin/g][Cout] fp32)."""
+    w = _f32(w)
+    Cout, Cin = w.shape[:2]
+    wq = np.empty((9, Cout, Cin), dtype=np.int8)
+    sw = np.empty((9, Cin // g, Cout), dtype=np.float32)
+    _load().oracle_quantize_filters(_p(w), Cin, Cout, g, _p(wq), _p(sw))
+    return wq, sw
+
+
+def direct_qconv(xq, sx, wq, sw, bias, N: int, H: int, W: int, g: int):
+    """Returns (y64, y32), both [N][H][W][Cout]."""
+    xq, wq = np.ascontiguousarray(xq, np.int8), np.ascontiguousarray(wq, np.int8)
+    sx, sw = _f32(sx), _f32(sw)
+    Cin, Cout = xq.shape[1], wq.shape[1]
+    assert xq.shape[0] == N * H * W and wq.shape == (9, Cout, Cin)
+    b = None if bias is None else _f32(bias)
+    y64 = np.empty((N, H, W, Cout), dtype=np.float64)
+    y32 = np.empty((N, H, W, Cout), dtype=np.float32)
+    _load().oracle_direct_qconv(_p(xq), _p(sx), _p(wq), _p(sw), _p(b), N, H, W, Cin, Cout, g,
+                                _p(y64), _p(y32))
+    return y64, y32
+
+
+def direct_pipeline(x, w, bias, g: int) -> dict:
+    """The whole group-wise quantized standard convolution."""
+    x = _f32(x)
+    N, H, W, _ = x.shape
+    xq, sx = quantize_pixels(x, g)
+    wq, sw = quantize_filters(w, g)
+    y64, y32 = direct_qconv(xq, sx, wq, sw, bias, N, H, W, g)
+    return dict(xq=xq, sx=sx, wq=wq, sw=sw, y64=y64, y=y32)

@@ -346,3 +346,75 @@ void oracle_contract_bruteforce(const int8_t *Xq, const int8_t *Wq, long T, int 
                         (int64_t)Xq[((size_t)t * T + tau) * Cin + c] *
                         (int64_t)Wq[((size_t)t * Cout + o) * Cin + c];
 }
+
+/* ======================================================================
+ * The comparison point of the paper's runtime section ("Runtime
+ * improvements": group-wise quantized STANDARD convolution layers): the same
+ * 3x3 stride-1 zero-pad-1 convolution with the same quantizer, but without
+ * the Winograd transforms.  Reading (the paper gives no formula for it):
+ * groups run along input channels as in the Winograd path; activations get
+ * one dynamic scale per (pixel, group), weights one scale per
+ * (filter tap, out-channel, group); every (tap, group) int32 dot product is
+ * rescaled by its two scales and summed:
+ *   y[b,h,w,o] = bias[o] + sum_{u,v} sum_G  P * sx[pixel(h+u-1,w+v-1)][G] * sw[u,v][G][o],
+ *   P = sum_{c in G} xq[pixel][c] * wq[u,v][o][c]          (exact int32).
+ * Layouts: xq [N*H*W][Cin] int8, sx [N*H*W][Cin/g] fp32,
+ *          wq [9][Cout][Cin] int8 (tap t = u*3+v), sw [9][Cin/g][Cout] fp32.
+ * ====================================================================== */
+void oracle_quantize_pixels(const float *x, long P, int Cin, int g, int8_t *xq, float *sx)
+{
+    const int groups = Cin / g;
+#pragma omp parallel for schedule(static)
+    for (long p = 0; p < P; ++p)
+        for (int gi = 0; gi < groups; ++gi)
+            sx[p * groups + gi] = quantize_group(x + (size_t)p * Cin + (size_t)gi * g, 1, g,
+                                                 xq + (size_t)p * Cin + (size_t)gi * g, 1);
+}
+
+void oracle_quantize_filters(const float *w, int Cin, int Cout, int g, int8_t *wq, float *sw)
+{
+    const int groups = Cin / g;
+    for (int t = 0; t < 9; ++t)
+        for (int o = 0; o < Cout; ++o)
+            for (int gi = 0; gi < groups; ++gi)
+                sw[((size_t)t * groups + gi) * Cout + o] =
+                    quantize_group(w + ((size_t)o * Cin + (size_t)gi * g) * 9 + t, 9, g,
+                                   wq + ((size_t)t * Cout + o) * Cin + (size_t)gi * g, 1);
+}
+
+/* y64 and y32 may each be NULL. */
+void oracle_direct_qconv(const int8_t *xq, const float *sx, const int8_t *wq, const float *sw,
+                         const float *bias, int N, int H, int W, int Cin, int Cout, int g,
+                         double *y64, float *y32)
+{
+    const int groups = Cin / g;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int b = 0; b < N; ++b)
+        for (int h = 0; h < H; ++h)
+            for (int q = 0; q < W; ++q)
+                for (int o = 0; o < Cout; ++o) {
+                    double acc = bias ? (double)bias[o] : 0.0;
+                    for (int u = 0; u < 3; ++u) {
+                        const int hh = h + u - 1;
+                        if (hh < 0 || hh >= H) continue;
+                        for (int v = 0; v < 3; ++v) {
+                            const int ww = q + v - 1;
+                            if (ww < 0 || ww >= W) continue;
+                            const size_t pix = ((size_t)b * H + hh) * W + ww;
+                            const int t = u * 3 + v;
+                            const int8_t *xr = xq + pix * Cin;
+                            const int8_t *wr = wq + ((size_t)t * Cout + o) * Cin;
+                            for (int gi = 0; gi < groups; ++gi) {
+                                int32_t p = 0;
+                                for (int c = gi * g; c < (gi + 1) * g; ++c)
+                                    p += (int32_t)xr[c] * (int32_t)wr[c];
+                                acc += (double)p * (double)sx[pix * groups + gi]
+                                                 * (double)sw[((size_t)t * groups + gi) * Cout + o];
+                            }
+                        }
+                    }
+                    const size_t idx = (((size_t)b * H + h) * W + q) * Cout + o;
+                    if (y64) y64[idx] = acc;
+                    if (y32) y32[idx] = (float)acc;
+                }
+}

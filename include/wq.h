@@ -138,6 +138,60 @@ wq_status_t wq_conv_forward_debug(const wq_plan_t *plan, void *stream, const flo
                                   void *workspace_dev, size_t workspace_bytes, float *y_dev,
                                   int32_t *P_dev, size_t P_bytes);
 
+/* ---------------------------------------------------------------------------
+ * The group-wise int8 quantized STANDARD 3x3 convolution (stride 1, zero pad 1)
+ * that the paper's Section "Runtime improvements" measures the quantized
+ * Winograd convolution against.  Same quantizer and the same groups along the
+ * input channels; no transforms:
+ *   activations: one dynamic scale per (pixel, group);
+ *   weights:     one scale per (filter tap t = u*3+v, output channel, group);
+ *   y[p][o] = bias[o] + sum_{t, group} float(int32 dot product over the group)
+ *                                      * sx[pixel shifted by tap t][group] * sw[t][group][o].
+ * Formats (device, sizes and offsets from wq_direct_plan_layout):
+ *   weight blob : Wq int8, blocked like the Winograd blob with 9 taps
+ *                 [9][Cout_pad/16][Cin/kstep][4][16][kstep/4]     at blob_Wq_off
+ *                 sW fp32 [9][groups][Cout_pad]                    at blob_sW_off
+ *                 bias fp32 [Cout_pad]                             at blob_bias_off
+ *   workspace   : xq int8 [N*H*W][Cin] (NHWC)                      at ws_xq_off
+ *                 sx fp32 [N*H*W][groups]                          at ws_sx_off
+ * Conventions as above: caller-owned device memory, calls enqueue on `stream`
+ * and never synchronise, every argument is checked on the host.  Errors:
+ * non-positive sizes, NULL pointers, Cin not a multiple of group_size ->
+ * INVALID_ARG; group_size not in {32,64,128,256,512} or a tensor of 2 GiB or
+ * more -> UNSUPPORTED; a buffer smaller than the layout says -> WORKSPACE;
+ * conv before weight_prepare -> NOT_PREPARED. */
+typedef struct wq_direct_plan wq_direct_plan_t;
+
+typedef struct {
+    int32_t N, H, W, Cin, Cout, group_size, groups, P, Cout_pad, kstep;
+    uint64_t blob_bytes, blob_Wq_off, blob_sW_off, blob_bias_off;
+    uint64_t ws_bytes, ws_xq_off, ws_sx_off;
+} wq_direct_layout_t;
+
+wq_status_t wq_direct_plan_create(wq_direct_plan_t **out, int N, int H, int W, int Cin, int Cout,
+                                  int group_size);
+wq_status_t wq_direct_plan_destroy(wq_direct_plan_t *plan);
+wq_status_t wq_direct_plan_layout(const wq_direct_plan_t *plan, wq_direct_layout_t *out);
+
+/* Offline: quantizes w_dev [Cout][Cin][3][3] fp32 per (tap, output channel,
+ * group) into the blob and copies bias_dev [Cout] (NULL = zeros). */
+wq_status_t wq_direct_weight_prepare(wq_direct_plan_t *plan, void *stream, const float *w_dev,
+                                     const float *bias_dev, void *weight_blob_dev, size_t blob_bytes);
+
+/* Dynamic activation quantization: x_dev [N][H][W][Cin] fp32 -> xq, sx in the workspace. */
+wq_status_t wq_direct_quantize(const wq_direct_plan_t *plan, void *stream, const float *x_dev,
+                               void *workspace_dev, size_t workspace_bytes);
+
+/* The convolution proper on the quantized operands; writes y_dev [N][H][W][Cout] fp32. */
+wq_status_t wq_direct_conv(const wq_direct_plan_t *plan, void *stream, const void *workspace_dev,
+                           size_t workspace_bytes, const void *weight_blob_dev, size_t blob_bytes,
+                           float *y_dev);
+
+/* wq_direct_quantize followed by wq_direct_conv. */
+wq_status_t wq_direct_forward(const wq_direct_plan_t *plan, void *stream, const float *x_dev,
+                              const void *weight_blob_dev, size_t blob_bytes, void *workspace_dev,
+                              size_t workspace_bytes, float *y_dev);
+
 const char *wq_status_string(wq_status_t status);
 
 #ifdef __cplusplus

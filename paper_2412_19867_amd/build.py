@@ -18,7 +18,7 @@ CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(ROOT, "_build")
 LIB = os.path.join(HERE, "libwq.so")
 SOURCES = ["wq_host.cpp", "wq_transform.hip", "wq_contract.hip", "wq_contract_m2.hip",
-           "wq_contract_m4.hip", "wq_contract_m6.hip", "wq_gemm_unfused.hip"]
+           "wq_contract_m4.hip", "wq_contract_m6.hip", "wq_gemm_unfused.hip", "wq_direct.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

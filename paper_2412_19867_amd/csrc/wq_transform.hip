@@ -428,6 +428,7 @@ hipError_t wq_launch_weight(const wq_plan *p, hipStream_t s, const float *w, con
                             int8_t *Wq, float *sW, float *bias_out) {
     hipError_t e;
     switch (p->m) {
+        case 1: e = launch_weight_m<1>(p, s, w, Wq, sW); break;   // F(1,3): the untransformed 3x3 taps
         case 2: e = launch_weight_m<2>(p, s, w, Wq, sW); break;
         case 4: e = launch_weight_m<4>(p, s, w, Wq, sW); break;
         default: e = launch_weight_m<6>(p, s, w, Wq, sW); break;

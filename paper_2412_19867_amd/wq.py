@@ -22,6 +22,8 @@ STATUS_NAMES = {0: "WQ_OK", 1: "WQ_ERR_INVALID_ARG", 2: "WQ_ERR_UNSUPPORTED",
 EXPORTS = ["wq_standard_transforms", "wq_plan_create", "wq_plan_destroy", "wq_plan_layout",
            "wq_weight_prepare", "wq_input_transform", "wq_contract_output", "wq_contract",
            "wq_output_transform", "wq_conv_forward",
+           "wq_direct_plan_create", "wq_direct_plan_destroy", "wq_direct_plan_layout",
+           "wq_direct_weight_prepare", "wq_direct_quantize", "wq_direct_conv", "wq_direct_forward",
            "wq_conv_forward_debug", "wq_status_string"]
 
 
@@ -32,6 +34,14 @@ class Layout(ctypes.Structure):
                 [(k, ctypes.c_uint64) for k in
                  ("blob_bytes", "blob_Wq_off", "blob_sW_off", "blob_bias_off",
                   "ws_bytes", "ws_Xq_off", "ws_sX_off", "ws_M_off", "debug_P_bytes")])
+
+
+class DirectLayout(ctypes.Structure):
+    _fields_ = ([(k, ctypes.c_int32) for k in
+                 ("N", "H", "W", "Cin", "Cout", "group_size", "groups", "P", "Cout_pad", "kstep")] +
+                [(k, ctypes.c_uint64) for k in
+                 ("blob_bytes", "blob_Wq_off", "blob_sW_off", "blob_bias_off",
+                  "ws_bytes", "ws_xq_off", "ws_sx_off")])
 
 
 class WqError(RuntimeError):
@@ -63,6 +73,13 @@ def lib() -> ctypes.CDLL:
         L.wq_output_transform.argtypes = [vp, vp, vp, sz, vp, sz, vp]
         L.wq_conv_forward.argtypes = [vp, vp, vp, vp, sz, vp, sz, vp]
         L.wq_conv_forward_debug.argtypes = [vp, vp, vp, vp, sz, vp, sz, vp, vp, sz]
+        L.wq_direct_plan_create.argtypes = [ctypes.POINTER(vp), ip, ip, ip, ip, ip, ip]
+        L.wq_direct_plan_destroy.argtypes = [vp]
+        L.wq_direct_plan_layout.argtypes = [vp, ctypes.POINTER(DirectLayout)]
+        L.wq_direct_weight_prepare.argtypes = [vp, vp, vp, vp, vp, sz]
+        L.wq_direct_quantize.argtypes = [vp, vp, vp, vp, sz]
+        L.wq_direct_conv.argtypes = [vp, vp, vp, sz, vp, sz, vp]
+        L.wq_direct_forward.argtypes = [vp, vp, vp, vp, sz, vp, sz, vp]
         L.wq_status_string.argtypes = [ip]
         L.wq_status_string.restype = ctypes.c_char_p
         for name in EXPORTS:
@@ -272,3 +289,92 @@ class Plan:
                                            _dev_ptr(y, torch.float32, "y", L.N * L.H * L.W * L.Cout),
                                            _dev_ptr(P, torch.int32, "P"), P.numel() * 4),
                "wq_conv_forward_debug")
+
+
+class DirectPlan:
+    """The group-wise quantized standard 3x3 convolution (the paper's runtime
+    comparison point) for one layer shape.  Owns only the host-side plan object."""
+
+    def __init__(self, N, H, W, Cin, Cout, group_size):
+        self._h = ctypes.c_void_p()
+        _check(lib().wq_direct_plan_create(ctypes.byref(self._h), N, H, W, Cin, Cout, group_size),
+               "wq_direct_plan_create")
+        self.layout = DirectLayout()
+        _check(lib().wq_direct_plan_layout(self._h, ctypes.byref(self.layout)), "wq_direct_plan_layout")
+
+    def __del__(self):
+        h = getattr(self, "_h", None)
+        if h and _lib is not None:
+            _lib.wq_direct_plan_destroy(h)
+            self._h = None
+
+    def alloc_blob(self, device="cuda"):
+        import torch
+        return torch.empty(self.layout.blob_bytes, dtype=torch.uint8, device=device)
+
+    def alloc_workspace(self, device="cuda"):
+        import torch
+        return torch.empty(self.layout.ws_bytes, dtype=torch.uint8, device=device)
+
+    def alloc_output(self, device="cuda"):
+        import torch
+        L = self.layout
+        return torch.empty((L.N, L.H, L.W, L.Cout), dtype=torch.float32, device=device)
+
+    def blob_views(self, blob):
+        """(Wq [9][Cout_pad][Cin] int8, sW [9][groups][Cout_pad] fp32, bias [Cout_pad]) - the int8
+        tensor un-blocked (a pure index permutation)."""
+        import torch
+        L = self.layout
+        R, ks = L.Cout_pad, L.kstep
+        raw = blob[L.blob_Wq_off:L.blob_Wq_off + 9 * R * L.Cin].view(torch.int8)
+        Wq = raw.view(9, R // 16, L.Cin // ks, 4, 16, ks // 4).permute(0, 1, 4, 2, 3, 5) \
+            .reshape(9, R, L.Cin)
+        sW = blob[L.blob_sW_off:L.blob_sW_off + 9 * L.groups * R * 4].view(torch.float32) \
+            .view(9, L.groups, R)
+        bias = blob[L.blob_bias_off:L.blob_bias_off + R * 4].view(torch.float32)
+        return Wq, sW, bias
+
+    def workspace_views(self, ws):
+        """(xq [P][Cin] int8, sx [P][groups] fp32)"""
+        import torch
+        L = self.layout
+        xq = ws[L.ws_xq_off:L.ws_xq_off + L.P * L.Cin].view(torch.int8).view(L.P, L.Cin)
+        sx = ws[L.ws_sx_off:L.ws_sx_off + L.P * L.groups * 4].view(torch.float32).view(L.P, L.groups)
+        return xq, sx
+
+    def weight_prepare(self, w, bias, blob, stream=None):
+        import torch
+        L = self.layout
+        wp = _dev_ptr(w, torch.float32, "w", L.Cout * L.Cin * 9)
+        bp = None if bias is None else _dev_ptr(bias, torch.float32, "bias", L.Cout)
+        _check(lib().wq_direct_weight_prepare(self._h, _stream_handle(stream), wp, bp,
+                                              _dev_ptr(blob, torch.uint8, "blob"), blob.numel()),
+               "wq_direct_weight_prepare")
+
+    def quantize(self, x, ws, stream=None):
+        import torch
+        L = self.layout
+        _check(lib().wq_direct_quantize(self._h, _stream_handle(stream),
+                                        _dev_ptr(x, torch.float32, "x", L.P * L.Cin),
+                                        _dev_ptr(ws, torch.uint8, "workspace"), ws.numel()),
+               "wq_direct_quantize")
+
+    def conv(self, ws, blob, y, stream=None):
+        import torch
+        L = self.layout
+        _check(lib().wq_direct_conv(self._h, _stream_handle(stream),
+                                    _dev_ptr(ws, torch.uint8, "workspace"), ws.numel(),
+                                    _dev_ptr(blob, torch.uint8, "blob"), blob.numel(),
+                                    _dev_ptr(y, torch.float32, "y", L.P * L.Cout)),
+               "wq_direct_conv")
+
+    def forward(self, x, blob, ws, y, stream=None):
+        import torch
+        L = self.layout
+        _check(lib().wq_direct_forward(self._h, _stream_handle(stream),
+                                       _dev_ptr(x, torch.float32, "x", L.P * L.Cin),
+                                       _dev_ptr(blob, torch.uint8, "blob"), blob.numel(),
+                                       _dev_ptr(ws, torch.uint8, "workspace"), ws.numel(),
+                                       _dev_ptr(y, torch.float32, "y", L.P * L.Cout)),
+               "wq_direct_forward")

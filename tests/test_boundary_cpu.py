@@ -128,3 +128,38 @@ def test_forward_errors_before_any_launch(wq):
         assert wq.status_string(code)
     with pytest.raises(wq.WqError):
         wq.Plan(1, 8, 8, 64, 64, 5, 32)
+
+
+def test_direct_plan_layout_and_argument_errors(wq):
+    p = wq.DirectPlan(2, 7, 9, 64, 40, 32)
+    L = p.layout
+    assert (L.P, L.groups, L.kstep) == (2 * 7 * 9, 2, 32)
+    assert L.Cout_pad % 32 == 0 and L.Cout_pad >= 40
+    assert L.blob_sW_off >= 9 * L.Cout_pad * 64 and L.blob_sW_off % 256 == 0
+    assert L.blob_bytes >= L.blob_bias_off + 4 * L.Cout_pad
+    assert L.ws_sx_off >= L.P * 64 and L.ws_bytes >= L.ws_sx_off + L.P * 2 * 4
+    lib = wq.lib()
+
+    def create(*a):
+        h = ctypes.c_void_p()
+        st = lib.wq_direct_plan_create(ctypes.byref(h), *a)
+        if st == 0:
+            lib.wq_direct_plan_destroy(h)
+        else:
+            assert not h.value
+        return st
+
+    assert create(1, 8, 8, 64, 64, 32) == 0
+    assert create(1, 8, 8, 64, 64, 48) == 2            # group size
+    assert create(1, 8, 8, 96, 64, 64) == 1            # Cin % g
+    assert create(0, 8, 8, 64, 64, 32) == 1
+    assert create(64, 1024, 1024, 64, 64, 32) == 2     # a tensor of 2 GiB or more
+    assert lib.wq_direct_plan_create(None, 1, 8, 8, 64, 64, 32) == 1
+    # calls without device buffers fail on the host
+    h = ctypes.c_void_p()
+    assert lib.wq_direct_plan_create(ctypes.byref(h), 1, 8, 8, 64, 64, 32) == 0
+    assert lib.wq_direct_quantize(h, None, None, None, 0) == 1
+    fake = ctypes.c_void_p(256)
+    assert lib.wq_direct_quantize(h, None, fake, fake, 16) == 5          # workspace too small
+    assert lib.wq_direct_conv(h, None, fake, 1 << 30, fake, 1 << 30, fake) == 4   # never prepared
+    lib.wq_direct_plan_destroy(h)

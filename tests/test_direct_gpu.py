@@ -1,0 +1,93 @@
+"""GPU parity of the group-wise quantized standard convolution against its oracle.
+
+Bit-exact on the int8 codes and the fp32 scales of activations and weights; fp32
+output within 1e-5 of the layer's largest output magnitude.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2412_19867_amd import workloads
+
+pytestmark = pytest.mark.gpu
+
+Y_TOL = 1e-5
+
+
+def run_direct(wq, x, w, bias, g):
+    N, H, W, Cin = x.shape
+    Cout = w.shape[0]
+    plan = wq.DirectPlan(N, H, W, Cin, Cout, g)
+    L = plan.layout
+    blob, ws, y = plan.alloc_blob(), plan.alloc_workspace(), plan.alloc_output()
+    y.fill_(float("nan"))
+    xd, wd = torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda()
+    bd = None if bias is None else torch.from_numpy(bias).cuda()
+    plan.weight_prepare(wd, bd, blob)
+    plan.forward(xd, blob, ws, y)
+    torch.cuda.synchronize()
+    Wq, sW, b = plan.blob_views(blob)
+    xq, sx = plan.workspace_views(ws)
+    return dict(wq=Wq[:, :Cout].cpu().numpy(), sw=sW[:, :, :Cout].cpu().numpy(),
+                xq=xq.cpu().numpy(), sx=sx.cpu().numpy(), y=y.cpu().numpy(),
+                pad_ok=bool((Wq[:, Cout:] == 0).all() and (sW[:, :, Cout:] == 0).all()
+                            and (b[Cout:] == 0).all()))
+
+
+def check_direct(wq, x, w, bias, g, name):
+    ref = oracle.direct_pipeline(x, w, bias, g)
+    got = run_direct(wq, x, w, bias, g)
+    assert got["pad_ok"]
+    for key in ("wq", "xq"):
+        bad = np.count_nonzero(got[key] != ref[key])
+        assert bad == 0, f"{name}: {key} differs in {bad} of {ref[key].size} codes"
+    for key in ("sw", "sx"):
+        assert np.array_equal(got[key].view(np.uint32), ref[key].view(np.uint32)), f"{name}: {key}"
+    assert np.isfinite(got["y"]).all(), f"{name}: y has unwritten or non-finite entries"
+    scale = np.abs(ref["y64"]).max()
+    err = np.abs(got["y"].astype(np.float64) - ref["y64"]).max()
+    assert err <= Y_TOL * scale, f"{name}: y max|err| {err:.3e} > {Y_TOL * scale:.3e}"
+    print(f"direct {name}: max|err|/max|y| = {err / max(scale, 1e-300):.2e}")
+
+
+SMALL = [
+    # seed N  H   W  Cin Cout  g
+    (1, 1, 8, 8, 32, 16, 32),
+    (2, 2, 7, 10, 64, 48, 32),        # pixels not a multiple of 64, Cout padded
+    (3, 1, 13, 6, 64, 33, 32),        # odd Cout
+    (4, 3, 9, 9, 128, 64, 64),
+    (5, 2, 12, 12, 256, 32, 128),
+    (6, 1, 6, 20, 512, 16, 256),
+    (7, 1, 4, 4, 512, 32, 512),
+    (8, 5, 11, 11, 96, 80, 32),       # several pixel tiles across image boundaries
+    (9, 1, 1, 1, 32, 1, 32),          # a single pixel
+    (10, 2, 3, 70, 64, 8, 64),        # rows longer than a pixel tile
+]
+
+
+@pytest.mark.parametrize("case", SMALL, ids=lambda c: "d%d_%dx%dx%d_%d-%d_g%d" % c)
+def test_direct_small_layers(wq, case):
+    seed, N, H, W, Cin, Cout, g = case
+    d = workloads.small_layer(seed, N, H, W, Cin, Cout, 4, g)
+    check_direct(wq, d.x, d.w, d.bias, g, "small%d" % seed)
+
+
+def test_direct_no_bias_and_zero_groups(wq):
+    d = workloads.small_layer(31, 2, 9, 7, 64, 32, 4, 32)
+    d.x[..., :32] = 0
+    d.x[0, 0, 0, 32:] *= np.float32(1e-41)      # a sub-normal group
+    check_direct(wq, d.x, d.w, None, 32, "nobias")
+
+
+def test_direct_config1(wq):
+    lay = workloads.CONFIGS[1][0]
+    d = workloads.make_layer_data(lay)
+    check_direct(wq, d.x, d.w, d.bias, lay.group_size, lay.name)
+
+
+@pytest.mark.parametrize("cfg,idx", [(2, 3), (3, 1), (4, 4)], ids=lambda v: str(v))
+def test_direct_config_layers_full_size(wq, cfg, idx):
+    lay = workloads.CONFIGS[cfg][idx]
+    d = workloads.make_layer_data(lay)
+    check_direct(wq, d.x, d.w, d.bias, lay.group_size, lay.name)

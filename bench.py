@@ -261,6 +261,33 @@ def main():
                                         hbm_frac=round(v["bytes"] / (v["us"] * 1e-6) / 1e9 / HBM_PEAK_GBS, 4))
                              for name, v in kernels.items()})
 
+    # ---- the paper's runtime comparison point on the same layers: the group-wise quantized
+    # standard (direct) convolution, same quantizer and groups, no transforms
+    d_items = []
+    for it in items:
+        lay = it["lay"]
+        dp = wq.DirectPlan(lay.N, lay.H, lay.W, lay.Cin, lay.Cout, lay.group_size)
+        dit = dict(plan=dp, blob=dp.alloc_blob(), ws=dp.alloc_workspace(), x=it["x"], y=it["y"])
+        dp.weight_prepare(it["w"], it["b"], dit["blob"])
+        d_items.append(dit)
+    torch.cuda.synchronize()
+
+    def direct_step():
+        for dit in d_items:
+            dit["plan"].forward(dit["x"], dit["blob"], dit["ws"], dit["y"])
+
+    sec_direct = timed_replays(capture(direct_step), max(10, args.steps // 2), 5)
+    dq_us = [kernel_us(lambda dit=dit: dit["plan"].quantize(dit["x"], dit["ws"])) for dit in d_items]
+    dc_us = [kernel_us(lambda dit=dit: dit["plan"].conv(dit["ws"], dit["blob"], dit["y"])) for dit in d_items]
+    direct = dict(value=round(direct_ops / sec_direct / 1e12, 2), unit="TOPS",
+                  ms_per_step=round(sec_direct * 1e3, 4),
+                  winograd_over_direct=round(sec_direct / sec, 3),
+                  layers=[dict(layer=it["lay"].name, quantize_us=round(dq_us[k], 2),
+                               conv_us=round(dc_us[k], 2)) for k, it in enumerate(items)])
+    # the step above overwrote y with the direct path's outputs; restore the Winograd results
+    step()
+    torch.cuda.synchronize()
+
     cpu_baseline = None
     if not args.no_cpu_baseline:
         import oracle
@@ -308,7 +335,7 @@ def main():
         config=dict(workload=f"configs[{args.config - 1}]: " + "; ".join(l.name for l in layers),
                     winograd=f"F({layers[0].m},3)", group_size=layers[0].group_size,
                     batch=layers[0].N, convs_per_step=n_convs),
-        roofline=roofline, cpu_baseline=cpu_baseline,
+        roofline=roofline, cpu_baseline=cpu_baseline, direct_conv_same_layers=direct,
         with_offline_stage=dict(value=round(direct_ops / sec_off / 1e12, 2), unit="TOPS",
                                 ms_per_step=round(sec_off * 1e3, 4)),
         layers=per_layer)

@@ -154,6 +154,7 @@ wq_status_t wq_conv_forward_debug(const wq_plan_t *plan, void *stream, const flo
  *                 bias fp32 [Cout_pad]                             at blob_bias_off
  *   workspace   : xq int8 [N*H*W][Cin] (NHWC)                      at ws_xq_off
  *                 sx fp32 [N*H*W][groups]                          at ws_sx_off
+ *                 partial sums fp32 [splits][N*H*W][Cout]          at ws_part_off (scratch, splits > 1)
  * Conventions as above: caller-owned device memory, calls enqueue on `stream`
  * and never synchronise, every argument is checked on the host.  Errors:
  * non-positive sizes, NULL pointers, Cin not a multiple of group_size ->
@@ -164,8 +165,9 @@ typedef struct wq_direct_plan wq_direct_plan_t;
 
 typedef struct {
     int32_t N, H, W, Cin, Cout, group_size, groups, P, Cout_pad, kstep;
+    int32_t splits, reserved; /* splits: workgroups sharing the 9 taps of an output tile (1, 3 or 9) */
     uint64_t blob_bytes, blob_Wq_off, blob_sW_off, blob_bias_off;
-    uint64_t ws_bytes, ws_xq_off, ws_sx_off;
+    uint64_t ws_bytes, ws_xq_off, ws_sx_off, ws_part_off;
 } wq_direct_layout_t;
 
 wq_status_t wq_direct_plan_create(wq_direct_plan_t **out, int N, int H, int W, int Cin, int Cout,
@@ -182,8 +184,9 @@ wq_status_t wq_direct_weight_prepare(wq_direct_plan_t *plan, void *stream, const
 wq_status_t wq_direct_quantize(const wq_direct_plan_t *plan, void *stream, const float *x_dev,
                                void *workspace_dev, size_t workspace_bytes);
 
-/* The convolution proper on the quantized operands; writes y_dev [N][H][W][Cout] fp32. */
-wq_status_t wq_direct_conv(const wq_direct_plan_t *plan, void *stream, const void *workspace_dev,
+/* The convolution proper on the quantized operands; writes y_dev [N][H][W][Cout] fp32.
+ * May use the partial-sum area of the workspace. */
+wq_status_t wq_direct_conv(const wq_direct_plan_t *plan, void *stream, void *workspace_dev,
                            size_t workspace_bytes, const void *weight_blob_dev, size_t blob_bytes,
                            float *y_dev);
 

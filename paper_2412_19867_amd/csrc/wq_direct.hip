@@ -25,6 +25,7 @@
 struct wq_direct_plan {
     wq_plan w;   // the offline weight stage as F(1,3): m = 1, n = 3, G = identity
     int N, H, W, Cin, Cout, g, groups, P, Cout_pad, kstep;
+    int splits;   // the 9 filter taps are shared out over this many workgroups per output tile (1, 3 or 9)
     wq_direct_layout_t lay;
     std::atomic<int> prepared;
 };
@@ -106,7 +107,8 @@ struct DArgs {
     const float *sW;
     const float *bias;
     float *y;
-    int N, H, W, Cin, Cout, Cout_pad, P, log2g;
+    float *part;   // splits > 1: partial sums [split][P][Cout], summed (+ bias) by k_direct_reduce
+    int N, H, W, Cin, Cout, Cout_pad, P, log2g, splits;
 };
 
 template <bool K64, bool CPG1>
@@ -183,10 +185,13 @@ __global__ __launch_bounds__(256, 2) void k_direct_conv(const DArgs a) {
 
     v4i pre[PD][LPT];
     float psc[PD];
-    // flat step index it = tap * cps + s
-    auto fetch = [&](int it, v4i (&dst)[LPT], float &dsc) {
-        const int t = it / cps, s = it - t * cps;   // uniform
-        const int dp = (t / 3 - 1) * W + (t % 3 - 1);
+    // the loader walks (tap t, K-step s) in order; its cursor is kept incrementally (uniform
+    // scalars) and stops at the last step, which the tail of the ring fetches again
+    // this workgroup's taps: [t_beg, t_end) (all 9, a row of the window, or a single tap)
+    const int tps = 9 / a.splits, t_beg = (int)blockIdx.z * tps, t_end = t_beg + tps;
+    int t_f = t_beg, s_f = 0, dp_f = (t_beg / 3 - 1) * W + (t_beg % 3 - 1);
+    auto fetch = [&](v4i (&dst)[LPT], float &dsc) {
+        const int t = t_f, s = s_f, dp = dp_f;
         const unsigned gam = (unsigned)(s * KSTEP) >> a.log2g;
         // pixels: row (prow + dp), bytes s*KSTEP + piece*16 ..
         const unsigned vX = ((nb >> t) & 1u)
@@ -205,6 +210,13 @@ __global__ __launch_bounds__(256, 2) void k_direct_conv(const DArgs a) {
                                                        : kInvalid);
         const unsigned so = sc_w ? ((unsigned)t * groups + gam) * (unsigned)Cout_pad * 4u : 0u;
         dsc = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(sc_w ? rSW : rSX, vs, so, 0));
+        if (!(t_f == t_end - 1 && s_f == cps - 1)) {   // advance unless this was the last step
+            if (++s_f == cps) {
+                s_f = 0;
+                ++t_f;
+                dp_f = (t_f == 3 || t_f == 6) ? dp_f + W - 2 : dp_f + 1;   // next row of the window, or next column
+            }
+        }
     };
     // LDS position of a gathered pixel piece in MFMA operand order [block][q][row16][KB bytes]
     const int xblk = 4 + (xr >> 4), xr16 = xr & 15;
@@ -234,9 +246,9 @@ __global__ __launch_bounds__(256, 2) void k_direct_conv(const DArgs a) {
             Mc[no][nt] = make_float4(0.f, 0.f, 0.f, 0.f);
         }
 
-    const int NI = 9 * cps, last = NI - 1;
+    const int NI = tps * cps;
 #pragma unroll
-    for (int u = 0; u < PD; ++u) fetch(min(u, last), pre[u], psc[u]);
+    for (int u = 0; u < PD; ++u) fetch(pre[u], psc[u]);
     commit(0, pre[0], psc[0]);
     __syncthreads();
     for (int i0 = 0; i0 < NI; i0 += PD) {
@@ -245,7 +257,7 @@ __global__ __launch_bounds__(256, 2) void k_direct_conv(const DArgs a) {
         const int it = i0 + u;
         if (it >= NI) break;
         const int buf = u & 1;   // PD is even, so it & 1 == u & 1
-        fetch(min(it + PD, last), pre[u], psc[u]);   // slot u held step it, already in LDS
+        fetch(pre[u], psc[u]);   // step it + PD (or the last one again); slot u held step it, already in LDS
         v4i av[2], bv[2];
 #pragma unroll
         for (int e = 0; e < 2; ++e) {
@@ -293,20 +305,43 @@ __global__ __launch_bounds__(256, 2) void k_direct_conv(const DArgs a) {
       }
     }
     // + bias, NHWC store: the lane holds channels 4q..4q+3 of pixel l16 in each block
+    const bool vec = (a.Cout & 3) == 0;   // rows of y are 16-byte aligned
+    const bool final_sum = a.splits == 1;
+    float *out = final_sum ? a.y : a.part + (size_t)blockIdx.z * P * a.Cout;
 #pragma unroll
     for (int no = 0; no < 2; ++no) {
         const int o = (ob0 + 2 * wn + no) * 16 + 4 * q;
+        float bv[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) bv[r] = (final_sum && o + r < a.Cout) ? a.bias[o + r] : 0.f;
 #pragma unroll
         for (int nt = 0; nt < 2; ++nt) {
             const int p = p0 + (2 * wm + nt) * 16 + l16;
-            if (p >= P) continue;
-            const float mv[4] = {Mc[no][nt].x, Mc[no][nt].y, Mc[no][nt].z, Mc[no][nt].w};
+            if (p >= P || o >= a.Cout) continue;
+            const float mv[4] = {Mc[no][nt].x + bv[0], Mc[no][nt].y + bv[1], Mc[no][nt].z + bv[2],
+                                 Mc[no][nt].w + bv[3]};
+            float *dst = out + (size_t)p * a.Cout + o;
+            if (vec) {   // o is a multiple of 4, so o + 3 < Cout too
+                __builtin_nontemporal_store(v4f{mv[0], mv[1], mv[2], mv[3]}, reinterpret_cast<v4f *>(dst));
+            } else {
 #pragma unroll
-            for (int r = 0; r < 4; ++r)
-                if (o + r < a.Cout)
-                    __builtin_nontemporal_store(mv[r] + a.bias[o + r], &a.y[(size_t)p * a.Cout + o + r]);
+                for (int r = 0; r < 4; ++r)
+                    if (o + r < a.Cout) __builtin_nontemporal_store(mv[r], dst + r);
+            }
         }
     }
+}
+
+// y = bias + sum of the per-split partial sums (splits > 1)
+__global__ __launch_bounds__(256) void k_direct_reduce(const float *__restrict__ part,
+                                                       const float *__restrict__ bias,
+                                                       float *__restrict__ y, int total, int Cout,
+                                                       int splits) {
+    const int e = blockIdx.x * 256 + threadIdx.x;
+    if (e >= total) return;
+    float acc = bias[e % Cout];
+    for (int z = 0; z < splits; ++z) acc += part[(size_t)z * total + e];
+    __builtin_nontemporal_store(acc, &y[e]);
 }
 
 int ilog2(int v) {
@@ -359,7 +394,17 @@ wq_status_t wq_direct_plan_create(wq_direct_plan_t **out, int N, int H, int W, i
     L.blob_bytes = L.blob_bias_off + align256((uint64_t)p->Cout_pad * 4);
     L.ws_xq_off = 0;
     L.ws_sx_off = align256((uint64_t)P * Cin);
-    L.ws_bytes = L.ws_sx_off + align256((uint64_t)P * p->groups * 4);
+    // few output tiles: share the taps out over 3 or 9 workgroups per tile (partial sums in the
+    // workspace, one more small kernel adds them) so that the chip has enough waves
+    const long long base = ((P + 63) / 64) * ((Cp + 63) / 64);
+    p->splits = base >= 512 ? 1 : (base * 3 >= 512 ? 3 : 9);
+    if (const char *e = std::getenv("WQ_DIRECT_SPLITS")) {
+        const int v = std::atoi(e);
+        if (v == 1 || v == 3 || v == 9) p->splits = v;
+    }
+    L.splits = p->splits;
+    L.ws_part_off = L.ws_sx_off + align256((uint64_t)P * p->groups * 4);
+    L.ws_bytes = L.ws_part_off + (p->splits > 1 ? align256((uint64_t)p->splits * P * Cout * 4) : 0);
     p->prepared.store(0);
     *out = p;
     return WQ_OK;
@@ -411,7 +456,7 @@ wq_status_t wq_direct_quantize(const wq_direct_plan_t *plan, void *stream, const
     return hipGetLastError() == hipSuccess ? WQ_OK : WQ_ERR_DEVICE;
 }
 
-wq_status_t wq_direct_conv(const wq_direct_plan_t *plan, void *stream, const void *workspace_dev,
+wq_status_t wq_direct_conv(const wq_direct_plan_t *plan, void *stream, void *workspace_dev,
                            size_t workspace_bytes, const void *weight_blob_dev, size_t blob_bytes,
                            float *y_dev) {
     if (!plan || !workspace_dev || !weight_blob_dev || !y_dev) return WQ_ERR_INVALID_ARG;
@@ -425,13 +470,22 @@ wq_status_t wq_direct_conv(const wq_direct_plan_t *plan, void *stream, const voi
     a.sW = (const float *)(b + plan->lay.blob_sW_off);
     a.bias = (const float *)(b + plan->lay.blob_bias_off);
     a.y = y_dev;
+    a.part = (float *)(const_cast<char *>(ws) + plan->lay.ws_part_off);
+    a.splits = plan->splits;
     a.N = plan->N; a.H = plan->H; a.W = plan->W; a.Cin = plan->Cin; a.Cout = plan->Cout;
     a.Cout_pad = plan->Cout_pad; a.P = plan->P; a.log2g = ilog2(plan->g);
-    const dim3 grid((unsigned)((plan->Cout_pad + 63) / 64), (unsigned)((plan->P + 63) / 64)), block(256);
+    const dim3 grid((unsigned)((plan->Cout_pad + 63) / 64), (unsigned)((plan->P + 63) / 64),
+                    (unsigned)plan->splits), block(256);
     hipStream_t s = (hipStream_t)stream;
     if (plan->kstep == 32) hipLaunchKernelGGL((k_direct_conv<false, true>), grid, block, 0, s, a);
     else if (plan->g == 64) hipLaunchKernelGGL((k_direct_conv<true, true>), grid, block, 0, s, a);
     else hipLaunchKernelGGL((k_direct_conv<true, false>), grid, block, 0, s, a);
+    if (hipGetLastError() != hipSuccess) return WQ_ERR_DEVICE;
+    if (plan->splits > 1) {
+        const int total = plan->P * plan->Cout;
+        hipLaunchKernelGGL(k_direct_reduce, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
+                           (const float *)a.part, a.bias, y_dev, total, plan->Cout, plan->splits);
+    }
     return hipGetLastError() == hipSuccess ? WQ_OK : WQ_ERR_DEVICE;
 }
 

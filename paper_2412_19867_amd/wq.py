@@ -38,10 +38,11 @@ class Layout(ctypes.Structure):
 
 class DirectLayout(ctypes.Structure):
     _fields_ = ([(k, ctypes.c_int32) for k in
-                 ("N", "H", "W", "Cin", "Cout", "group_size", "groups", "P", "Cout_pad", "kstep")] +
+                 ("N", "H", "W", "Cin", "Cout", "group_size", "groups", "P", "Cout_pad", "kstep",
+                  "splits", "reserved")] +
                 [(k, ctypes.c_uint64) for k in
                  ("blob_bytes", "blob_Wq_off", "blob_sW_off", "blob_bias_off",
-                  "ws_bytes", "ws_xq_off", "ws_sx_off")])
+                  "ws_bytes", "ws_xq_off", "ws_sx_off", "ws_part_off")])
 
 
 class WqError(RuntimeError):

@@ -74,6 +74,11 @@ def _layers() -> Dict[int, List[Layer]]:
     sdxl = [(128, 320), (64, 640), (32, 1280)]
     out[5] = [Layer(5, i, 2, s, s, c, c, 4, 64, "student_t3_outlier30", "normal002", repeat=4)
               for i, (s, c) in enumerate(sdxl)]
+    # Not one of the five benchmark configurations: one large GEMM-shaped layer (2048 tiles,
+    # 1280 -> 1280 channels) at two group sizes, to show what the contraction kernel reaches when
+    # the per-tap matrices are big.  Timing only; the oracle would need minutes for it.
+    out[6] = [Layer(6, i, 32, 32, 32, 1280, 1280, 4, g, "student_t3_outlier30", "normal002")
+              for i, g in enumerate([64, 256])]
     return out
 
 

@@ -79,8 +79,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
-                 "(the path shards without communication over tiles or output channels; "
-                 "see DESIGN.md)")
+                 "(the path would shard without communication over tiles or output channels)")
 
     import numpy as np
     import torch

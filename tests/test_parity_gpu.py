@@ -221,3 +221,15 @@ def test_graph_replay_matches_eager(wq):
         plan.forward(x, blob, ws, y_eager)           # eager run of the same plan in between
         torch.cuda.synchronize()
         assert torch.equal(y_eager, want)
+
+
+@pytest.mark.parametrize("idx", [0, 1], ids=["g64", "g256"])
+def test_wide_layer_at_reduced_batch(wq, idx):
+    """The extra 1280 -> 1280 layer of the benchmark (two-kernel form because of its width;
+    groups of 256 accumulate four K-steps per group) with batch 4 instead of 32."""
+    lay = workloads.CONFIGS[6][idx]
+    import dataclasses
+    d = workloads.make_layer_data(lay, N=4)
+    d.layer = dataclasses.replace(lay, N=4)
+    assert wq.Plan(4, lay.H, lay.W, lay.Cin, lay.Cout, lay.m, lay.group_size).layout.k2_kernels == 2
+    check(wq, d, want_P=False)

@@ -37,7 +37,6 @@ typedef int v2i __attribute__((ext_vector_type(2)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 constexpr int kBufFlags = 0x00020000;
 constexpr unsigned kInvalid = 1u << 31;   // an offset past the end of any buffer (all < 2 GiB): loads 0
-constexpr int kWriteThrough = 17;         // cache policy sc0 sc1: written through while the kernel runs
 
 template <int CTRL>
 __device__ __forceinline__ uint32_t dpp_max(uint32_t v) {

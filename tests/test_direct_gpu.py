@@ -91,3 +91,20 @@ def test_direct_config_layers_full_size(wq, cfg, idx):
     lay = workloads.CONFIGS[cfg][idx]
     d = workloads.make_layer_data(lay)
     check_direct(wq, d.x, d.w, d.bias, lay.group_size, lay.name)
+
+
+def _random_cases(count, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for k in range(count):
+        g = int(rng.choice([32, 32, 64, 128]))
+        cases.append((2000 + k, int(rng.integers(1, 4)), int(rng.integers(1, 20)), int(rng.integers(1, 20)),
+                      g * int(rng.integers(1, 5)), int(rng.integers(1, 100)), g))
+    return cases
+
+
+@pytest.mark.parametrize("case", _random_cases(12, 2025), ids=lambda c: "r%d_%dx%dx%d_%d-%d_g%d" % c)
+def test_direct_random_small_shapes(wq, case):
+    seed, N, H, W, Cin, Cout, g = case
+    d = workloads.small_layer(seed, N, H, W, Cin, Cout, 4, g)
+    check_direct(wq, d.x, d.w, d.bias, g, "random%d" % seed)

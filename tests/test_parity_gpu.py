@@ -233,3 +233,23 @@ def test_wide_layer_at_reduced_batch(wq, idx):
     d.layer = dataclasses.replace(lay, N=4)
     assert wq.Plan(4, lay.H, lay.W, lay.Cin, lay.Cout, lay.m, lay.group_size).layout.k2_kernels == 2
     check(wq, d, want_P=False)
+
+
+def _random_cases(count, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for k in range(count):
+        m = int(rng.choice([2, 4, 6]))
+        g = int(rng.choice([32, 32, 64, 128]))
+        Cin = g * int(rng.integers(1, 5))
+        cases.append((1000 + k, int(rng.integers(1, 4)), int(rng.integers(1, 20)), int(rng.integers(1, 20)),
+                      Cin, int(rng.integers(1, 100)), m, g, bool(rng.integers(0, 2))))
+    return cases
+
+
+@pytest.mark.parametrize("case", _random_cases(24, 2024), ids=lambda c: "r%d_%dx%dx%d_%d-%d_F%d_g%d" % c[:8])
+def test_random_small_shapes(wq, case):
+    """Seeded random shapes: image sizes from 1 to 19, any Cout, one to four groups."""
+    seed, N, H, W, Cin, Cout, m, g, scaled = case
+    d = workloads.small_layer(seed, N, H, W, Cin, Cout, m, g, row_scales=scaled)
+    check(wq, d)

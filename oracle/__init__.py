@@ -210,3 +210,29 @@ def direct_pipeline(x, w, bias, g: int) -> dict:
     wq, sw = quantize_filters(w, g)
     y64, y32 = direct_qconv(xq, sx, wq, sw, bias, N, H, W, g)
     return dict(xq=xq, sx=sx, wq=wq, sw=sw, y64=y64, y=y32)
+
+
+# ---- group-wise quantized linear layer (the 1-tap case of the same quantized GEMM)
+def quantize_weight_rows(w, g: int):
+    """w [Cout][Cin] fp32 -> (wq [Cout][Cin] int8, sw [Cin/g][Cout] fp32)."""
+    w = _f32(w)
+    Cout, Cin = w.shape
+    wq = np.empty((Cout, Cin), dtype=np.int8)
+    sw = np.empty((Cin // g, Cout), dtype=np.float32)
+    _load().oracle_quantize_weight_rows(_p(w), Cin, Cout, g, _p(wq), _p(sw))
+    return wq, sw
+
+
+def linear_pipeline(x, w, bias, g: int) -> dict:
+    """x [R][Cin], w [Cout][Cin]: quantize both group-wise, multiply, rescale per group."""
+    x, w = _f32(x), _f32(w)
+    R, Cin = x.shape
+    Cout = w.shape[0]
+    xq, sx = quantize_pixels(x, g)
+    wq, sw = quantize_weight_rows(w, g)
+    b = None if bias is None else _f32(bias)
+    y64 = np.empty((R, Cout), dtype=np.float64)
+    y32 = np.empty((R, Cout), dtype=np.float32)
+    _load().oracle_linear_q(_p(xq), _p(sx), _p(wq), _p(sw), _p(b), ctypes.c_long(R), Cin, Cout, g,
+                            _p(y64), _p(y32))
+    return dict(xq=xq, sx=sx, wq=wq, sw=sw, y64=y64, y=y32)

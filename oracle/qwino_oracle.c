@@ -418,3 +418,41 @@ void oracle_direct_qconv(const int8_t *xq, const float *sx, const int8_t *wq, co
                     if (y32) y32[idx] = (float)acc;
                 }
 }
+
+/* ======================================================================
+ * Group-wise quantized linear layer y = x W^T + bias (the paper applies the
+ * same group-wise quantization to all linear layers and to the attention
+ * matrix products, Section "Experiments", first paragraph): rows of x
+ * [R][Cin] get one dynamic scale per (row, group) - oracle_quantize_pixels
+ * with P = R - and the weight matrix W [Cout][Cin] one scale per
+ * (output row, group):  y[r][o] = bias[o] + sum_G P * sx[r][G] * sw[G][o].
+ * Layouts: wq [Cout][Cin] int8, sw [Cin/g][Cout] fp32.
+ * ====================================================================== */
+void oracle_quantize_weight_rows(const float *w, int Cin, int Cout, int g, int8_t *wq, float *sw)
+{
+    const int groups = Cin / g;
+    for (int o = 0; o < Cout; ++o)
+        for (int gi = 0; gi < groups; ++gi)
+            sw[(size_t)gi * Cout + o] = quantize_group(w + (size_t)o * Cin + (size_t)gi * g, 1, g,
+                                                       wq + (size_t)o * Cin + (size_t)gi * g, 1);
+}
+
+/* y64 and y32 may each be NULL. */
+void oracle_linear_q(const int8_t *xq, const float *sx, const int8_t *wq, const float *sw,
+                     const float *bias, long R, int Cin, int Cout, int g, double *y64, float *y32)
+{
+    const int groups = Cin / g;
+#pragma omp parallel for schedule(static)
+    for (long r = 0; r < R; ++r)
+        for (int o = 0; o < Cout; ++o) {
+            double acc = bias ? (double)bias[o] : 0.0;
+            for (int gi = 0; gi < groups; ++gi) {
+                int32_t p = 0;
+                for (int c = gi * g; c < (gi + 1) * g; ++c)
+                    p += (int32_t)xq[(size_t)r * Cin + c] * (int32_t)wq[(size_t)o * Cin + c];
+                acc += (double)p * (double)sx[(size_t)r * groups + gi] * (double)sw[(size_t)gi * Cout + o];
+            }
+            if (y64) y64[(size_t)r * Cout + o] = acc;
+            if (y32) y32[(size_t)r * Cout + o] = (float)acc;
+        }
+}

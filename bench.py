@@ -297,6 +297,18 @@ def main():
     step()
     torch.cuda.synchronize()
 
+    # ---- the same quantized GEMM core as a linear layer (one tap): one attention-sized projection
+    lin_R, lin_C, lin_g = 4096, 1280, 64
+    lp = wq.DirectPlan(lin_R, 1, 1, lin_C, lin_C, lin_g, linear=True)
+    lblob, lws, ly = lp.alloc_blob(), lp.alloc_workspace(), lp.alloc_output()
+    lx = torch.randn(lin_R, lin_C, device="cuda")
+    lp.weight_prepare(torch.randn(lin_C, lin_C, device="cuda") * 0.02, None, lblob)
+    lq_us = kernel_us(lambda: lp.quantize(lx, lws))
+    lc_us = kernel_us(lambda: lp.conv(lws, lblob, ly))
+    linear = dict(shape=f"{lin_R}x{lin_C}->{lin_C}, g={lin_g}", quantize_us=round(lq_us, 2),
+                  gemm_us=round(lc_us, 2),
+                  int8_tops=round(2 * lin_R * lin_C * lin_C / ((lq_us + lc_us) * 1e-6) / 1e12, 1))
+
     cpu_baseline = None
     if not args.no_cpu_baseline and args.config != 6:
         import oracle
@@ -345,6 +357,7 @@ def main():
                     winograd=f"F({layers[0].m},3)", group_size=layers[0].group_size,
                     batch=layers[0].N, convs_per_step=n_convs),
         roofline=roofline, cpu_baseline=cpu_baseline, direct_conv_same_layers=direct,
+        quantized_linear_layer=linear,
         with_offline_stage=dict(value=round(direct_ops / sec_off / 1e12, 2), unit="TOPS",
                                 ms_per_step=round(sec_off * 1e3, 4)),
         layers=per_layer)

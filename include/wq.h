@@ -148,9 +148,9 @@ wq_status_t wq_conv_forward_debug(const wq_plan_t *plan, void *stream, const flo
  *   y[p][o] = bias[o] + sum_{t, group} float(int32 dot product over the group)
  *                                      * sx[pixel shifted by tap t][group] * sw[t][group][o].
  * Formats (device, sizes and offsets from wq_direct_plan_layout):
- *   weight blob : Wq int8, blocked like the Winograd blob with 9 taps
- *                 [9][Cout_pad/16][Cin/kstep][4][16][kstep/4]     at blob_Wq_off
- *                 sW fp32 [9][groups][Cout_pad]                    at blob_sW_off
+ *   weight blob : Wq int8, blocked like the Winograd blob with `taps` taps
+ *                 [taps][Cout_pad/16][Cin/kstep][4][16][kstep/4]  at blob_Wq_off
+ *                 sW fp32 [taps][groups][Cout_pad]                 at blob_sW_off
  *                 bias fp32 [Cout_pad]                             at blob_bias_off
  *   workspace   : xq int8 [N*H*W][Cin] (NHWC)                      at ws_xq_off
  *                 sx fp32 [N*H*W][groups]                          at ws_sx_off
@@ -165,13 +165,21 @@ typedef struct wq_direct_plan wq_direct_plan_t;
 
 typedef struct {
     int32_t N, H, W, Cin, Cout, group_size, groups, P, Cout_pad, kstep;
-    int32_t splits, reserved; /* splits: workgroups sharing the 9 taps of an output tile (1, 3 or 9) */
+    int32_t splits, taps; /* splits: workgroups sharing the 9 taps of an output tile (1, 3 or 9);
+                             taps: 9 for the 3x3 convolution, 1 for a linear layer */
     uint64_t blob_bytes, blob_Wq_off, blob_sW_off, blob_bias_off;
     uint64_t ws_bytes, ws_xq_off, ws_sx_off, ws_part_off;
 } wq_direct_layout_t;
 
 wq_status_t wq_direct_plan_create(wq_direct_plan_t **out, int N, int H, int W, int Cin, int Cout,
                                   int group_size);
+/* The same plan type for a group-wise quantized LINEAR layer y = x W^T + bias (the paper
+ * quantizes every linear layer and attention product the same way, Section "Experiments"):
+ * x [R][Cin] fp32 with one dynamic scale per (row, group), W [Cout][Cin] fp32 with one scale
+ * per (output row, group), y [R][Cout] fp32.  It is the one-tap case of the convolution above:
+ * use wq_direct_weight_prepare (w_dev is then [Cout][Cin]), wq_direct_quantize,
+ * wq_direct_conv and wq_direct_forward with N*H*W = R; the layout has taps = 1. */
+wq_status_t wq_linear_plan_create(wq_direct_plan_t **out, int R, int Cin, int Cout, int group_size);
 wq_status_t wq_direct_plan_destroy(wq_direct_plan_t *plan);
 wq_status_t wq_direct_plan_layout(const wq_direct_plan_t *plan, wq_direct_layout_t *out);
 

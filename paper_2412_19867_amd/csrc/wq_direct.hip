@@ -25,6 +25,7 @@
 struct wq_direct_plan {
     wq_plan w;   // the offline weight stage as F(1,3): m = 1, n = 3, G = identity
     int N, H, W, Cin, Cout, g, groups, P, Cout_pad, kstep;
+    int taps;     // 9 = 3x3 convolution, 1 = linear layer (every row is its own "image")
     int splits;   // the 9 filter taps are shared out over this many workgroups per output tile (1, 3 or 9)
     wq_direct_layout_t lay;
     std::atomic<int> prepared;
@@ -107,7 +108,7 @@ struct DArgs {
     const float *bias;
     float *y;
     float *part;   // splits > 1: partial sums [split][P][Cout], summed (+ bias) by k_direct_reduce
-    int N, H, W, Cin, Cout, Cout_pad, P, log2g, splits;
+    int N, H, W, Cin, Cout, Cout_pad, P, log2g, splits, taps;
 };
 
 template <bool K64, bool CPG1>
@@ -127,11 +128,11 @@ __global__ __launch_bounds__(256, 2) void k_direct_conv(const DArgs a) {
     const int cpg_mask = ((1 << a.log2g) / KSTEP) - 1;
 
     const __amdgpu_buffer_rsrc_t rW = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<int8_t *>(a.Wq), 0, (int)(9u * (unsigned)Cout_pad * (unsigned)Cin), kBufFlags);
+        const_cast<int8_t *>(a.Wq), 0, (int)((unsigned)a.taps * (unsigned)Cout_pad * (unsigned)Cin), kBufFlags);
     const __amdgpu_buffer_rsrc_t rX = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<int8_t *>(a.xq), 0, (int)((unsigned)P * (unsigned)Cin), kBufFlags);
     const __amdgpu_buffer_rsrc_t rSW = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<float *>(a.sW), 0, (int)(9u * (unsigned)groups * (unsigned)Cout_pad * 4u), kBufFlags);
+        const_cast<float *>(a.sW), 0, (int)((unsigned)a.taps * (unsigned)groups * (unsigned)Cout_pad * 4u), kBufFlags);
     const __amdgpu_buffer_rsrc_t rSX = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<float *>(a.sx), 0, (int)((unsigned)P * (unsigned)groups * 4u), kBufFlags);
 
@@ -155,6 +156,8 @@ __global__ __launch_bounds__(256, 2) void k_direct_conv(const DArgs a) {
         const int pc = min(prow, P - 1);
         const int ww = pc % W, hh = (pc / W) % H;
         if (prow < P) {
+            if (a.taps == 1) nb = 1u;   // linear layer: the row itself
+            else
 #pragma unroll
             for (int u = 0; u < 3; ++u)
 #pragma unroll
@@ -172,6 +175,8 @@ __global__ __launch_bounds__(256, 2) void k_direct_conv(const DArgs a) {
         const int pc = min(prow_s, P - 1);
         const int ww = pc % W, hh = (pc / W) % H;
         if (prow_s < P) {
+            if (a.taps == 1) nb_s = 1u;
+            else
 #pragma unroll
             for (int u = 0; u < 3; ++u)
 #pragma unroll
@@ -187,8 +192,8 @@ __global__ __launch_bounds__(256, 2) void k_direct_conv(const DArgs a) {
     // the loader walks (tap t, K-step s) in order; its cursor is kept incrementally (uniform
     // scalars) and stops at the last step, which the tail of the ring fetches again
     // this workgroup's taps: [t_beg, t_end) (all 9, a row of the window, or a single tap)
-    const int tps = 9 / a.splits, t_beg = (int)blockIdx.z * tps, t_end = t_beg + tps;
-    int t_f = t_beg, s_f = 0, dp_f = (t_beg / 3 - 1) * W + (t_beg % 3 - 1);
+    const int tps = a.taps / a.splits, t_beg = (int)blockIdx.z * tps, t_end = t_beg + tps;
+    int t_f = t_beg, s_f = 0, dp_f = a.taps == 1 ? 0 : (t_beg / 3 - 1) * W + (t_beg % 3 - 1);
     auto fetch = [&](v4i (&dst)[LPT], float &dsc) {
         const int t = t_f, s = s_f, dp = dp_f;
         const unsigned gam = (unsigned)(s * KSTEP) >> a.log2g;
@@ -356,8 +361,8 @@ uint64_t align256(uint64_t v) { return (v + 255) / 256 * 256; }
 // ------------------------------------------------------------------ C ABI
 extern "C" {
 
-wq_status_t wq_direct_plan_create(wq_direct_plan_t **out, int N, int H, int W, int Cin, int Cout,
-                                  int group_size) {
+static wq_status_t make_plan(wq_direct_plan_t **out, int N, int H, int W, int Cin, int Cout,
+                             int group_size, int taps) {
     if (!out) return WQ_ERR_INVALID_ARG;
     *out = nullptr;
     if (N <= 0 || H <= 0 || W <= 0 || Cin <= 0 || Cout <= 0 || group_size <= 0) return WQ_ERR_INVALID_ARG;
@@ -365,14 +370,15 @@ wq_status_t wq_direct_plan_create(wq_direct_plan_t **out, int N, int H, int W, i
         return WQ_ERR_UNSUPPORTED;
     if (Cin % group_size != 0) return WQ_ERR_INVALID_ARG;
     const long long P = (long long)N * H * W, Cp = (Cout + 31) / 32 * 32, lim = (1LL << 31) - 1;
-    if (P * Cin * 4 > lim || P * Cout * 4 > lim || 9 * Cp * Cin > lim ||
-        9 * Cp * (Cin / group_size) * 4 > lim)
+    if (P * Cin * 4 > lim || P * Cout * 4 > lim || taps * Cp * Cin > lim ||
+        taps * Cp * (Cin / group_size) * 4 > lim)
         return WQ_ERR_UNSUPPORTED;
     wq_direct_plan *p = new (std::nothrow) wq_direct_plan();
     if (!p) return WQ_ERR_INVALID_ARG;
     p->N = N; p->H = H; p->W = W; p->Cin = Cin; p->Cout = Cout; p->g = group_size;
     p->groups = Cin / group_size; p->P = (int)P; p->Cout_pad = (int)Cp;
     p->kstep = group_size == 32 ? 32 : 64;
+    p->taps = taps;
     // the weight stage: the offline Winograd weight kernel as F(1,3) with G = I leaves the nine
     // filter taps untransformed and quantizes them per (tap, out-channel, group)
     wq_plan &w = p->w;
@@ -387,9 +393,10 @@ wq_status_t wq_direct_plan_create(wq_direct_plan_t **out, int N, int H, int W, i
     wq_direct_layout_t &L = p->lay;
     L.N = N; L.H = H; L.W = W; L.Cin = Cin; L.Cout = Cout; L.group_size = group_size;
     L.groups = p->groups; L.P = p->P; L.Cout_pad = p->Cout_pad; L.kstep = p->kstep;
+    L.taps = taps;
     L.blob_Wq_off = 0;
-    L.blob_sW_off = align256(9ull * p->Cout_pad * Cin);
-    L.blob_bias_off = L.blob_sW_off + align256(9ull * p->groups * p->Cout_pad * 4);
+    L.blob_sW_off = align256((uint64_t)taps * p->Cout_pad * Cin);
+    L.blob_bias_off = L.blob_sW_off + align256((uint64_t)taps * p->groups * p->Cout_pad * 4);
     L.blob_bytes = L.blob_bias_off + align256((uint64_t)p->Cout_pad * 4);
     L.ws_xq_off = 0;
     L.ws_sx_off = align256((uint64_t)P * Cin);
@@ -401,12 +408,22 @@ wq_status_t wq_direct_plan_create(wq_direct_plan_t **out, int N, int H, int W, i
         const int v = std::atoi(e);
         if (v == 1 || v == 3 || v == 9) p->splits = v;
     }
+    if (taps == 1) p->splits = 1;
     L.splits = p->splits;
     L.ws_part_off = L.ws_sx_off + align256((uint64_t)P * p->groups * 4);
     L.ws_bytes = L.ws_part_off + (p->splits > 1 ? align256((uint64_t)p->splits * P * Cout * 4) : 0);
     p->prepared.store(0);
     *out = p;
     return WQ_OK;
+}
+
+wq_status_t wq_direct_plan_create(wq_direct_plan_t **out, int N, int H, int W, int Cin, int Cout,
+                                  int group_size) {
+    return make_plan(out, N, H, W, Cin, Cout, group_size, 9);
+}
+
+wq_status_t wq_linear_plan_create(wq_direct_plan_t **out, int R, int Cin, int Cout, int group_size) {
+    return make_plan(out, R, 1, 1, Cin, Cout, group_size, 1);
 }
 
 wq_status_t wq_direct_plan_destroy(wq_direct_plan_t *plan) {
@@ -426,10 +443,9 @@ wq_status_t wq_direct_weight_prepare(wq_direct_plan_t *plan, void *stream, const
     if (!plan || !w_dev || !weight_blob_dev) return WQ_ERR_INVALID_ARG;
     if (blob_bytes < plan->lay.blob_bytes) return WQ_ERR_WORKSPACE;
     char *b = (char *)weight_blob_dev;
-    hipError_t e = wq_launch_weight(&plan->w, (hipStream_t)stream, w_dev, bias_dev,
-                                    (int8_t *)(b + plan->lay.blob_Wq_off),
-                                    (float *)(b + plan->lay.blob_sW_off),
-                                    (float *)(b + plan->lay.blob_bias_off));
+    hipError_t e = (plan->taps == 1 ? wq_launch_weight_rows : wq_launch_weight)(
+        &plan->w, (hipStream_t)stream, w_dev, bias_dev, (int8_t *)(b + plan->lay.blob_Wq_off),
+        (float *)(b + plan->lay.blob_sW_off), (float *)(b + plan->lay.blob_bias_off));
     if (e != hipSuccess) return WQ_ERR_DEVICE;
     plan->prepared.store(1);
     return WQ_OK;
@@ -471,6 +487,7 @@ wq_status_t wq_direct_conv(const wq_direct_plan_t *plan, void *stream, void *wor
     a.y = y_dev;
     a.part = (float *)(const_cast<char *>(ws) + plan->lay.ws_part_off);
     a.splits = plan->splits;
+    a.taps = plan->taps;
     a.N = plan->N; a.H = plan->H; a.W = plan->W; a.Cin = plan->Cin; a.Cout = plan->Cout;
     a.Cout_pad = plan->Cout_pad; a.P = plan->P; a.log2g = ilog2(plan->g);
     const dim3 grid((unsigned)((plan->Cout_pad + 63) / 64), (unsigned)((plan->P + 63) / 64),

@@ -80,6 +80,9 @@ __device__ __forceinline__ void wq_apply_at(const wq_xf &xf, const float (&v)[M 
 // Kernel launchers (each enqueues on `s` and returns the launch status).
 hipError_t wq_launch_weight(const wq_plan *p, hipStream_t s, const float *w, const float *bias,
                             int8_t *Wq, float *sW, float *bias_out);
+// w [Cout][Cin] without a transform (one tap): linear layers
+hipError_t wq_launch_weight_rows(const wq_plan *p, hipStream_t s, const float *w, const float *bias,
+                                 int8_t *Wq, float *sW, float *bias_out);
 hipError_t wq_launch_input(const wq_plan *p, hipStream_t s, const float *x, int8_t *Xq, float *sX);
 // Mbuf: fp32 scratch [T_pad][taps][Cout_pad] inside the workspace, used by the two-kernel path
 hipError_t wq_launch_contract(const wq_plan *p, hipStream_t s, const int8_t *Xq, const float *sX,

@@ -380,6 +380,40 @@ __global__ void k_copy_bias(const float *__restrict__ bias, float *__restrict__ 
     if (o < Cout_pad) out[o] = (bias && o < Cout) ? bias[o] : 0.0f;
 }
 
+// Group-wise quantization of a plain weight matrix w [Cout][Cin] (a linear layer, or a 1x1
+// convolution): the offline weight stage without a transform, one tap.
+__global__ __launch_bounds__(256) void k_quantize_weight_rows(const float *__restrict__ w,
+                                                              int8_t *__restrict__ Wq,
+                                                              float *__restrict__ sW, int Cin, int Cout,
+                                                              int Cout_pad, int log2k, int kstep_log2) {
+    __shared__ uint4 amax_s[1][16];
+    __shared__ float r_s[1][16];
+    __shared__ __attribute__((aligned(16))) char codes_s[kTapStride];
+    const int tid = threadIdx.x, row = tid >> 4, l16 = tid & 15;
+    const int k = 1 << log2k;
+    const int CC = Cin >> 5, groups = CC >> log2k;
+    const int rb = blockIdx.x / CC, rem = blockIdx.x % CC;
+    const int sub = rem / groups, gam = rem % groups;
+    const int row16 = sub * (16 >> log2k) + (row >> log2k);
+    const int chunk = gam * k + (row & (k - 1));
+    const int o = rb * 16 + row16;
+    float2 X[1];
+    X[0] = o < Cout ? *reinterpret_cast<const float2 *>(w + (size_t)o * Cin + chunk * 32 + l16 * 2)
+                    : make_float2(0.0f, 0.0f);
+    reinterpret_cast<uint32_t *>(&amax_s[0][row])[l16 >> 2] = quad_max(abs_max_bits(X[0].x, X[0].y));
+    const __amdgpu_buffer_rsrc_t rq = __builtin_amdgcn_make_buffer_rsrc(
+        Wq, 0, (int)((unsigned)Cout_pad * (unsigned)Cin), kBufFlags);
+    const CodePlace place =
+        code_place(tid, kstep_log2, (unsigned)rb * 16u * (unsigned)Cin, [&](int r, int &c, int &r16) {
+            c = gam * k + (r & (k - 1));
+            r16 = sub * (16 >> log2k) + (r >> log2k);
+        });
+    const long scale_base = (long)gam * Cout_pad + rb * 16 + sub * (16 >> log2k);
+    quantize_and_store<1>(X, amax_s, r_s, codes_s, log2k, 0, rq, place,
+                          (unsigned)Cout_pad * (unsigned)Cin, sW, scale_base,
+                          (long)groups * Cout_pad, 16);
+}
+
 int ilog2(int v) {
     int l = 0;
     while ((1 << l) < v) ++l;
@@ -422,6 +456,17 @@ hipError_t wq_launch_input(const wq_plan *p, hipStream_t s, const float *x, int8
         case 4: return launch_input_m<4>(p, s, x, Xq, sX);
         default: return launch_input_m<6>(p, s, x, Xq, sX);
     }
+}
+
+hipError_t wq_launch_weight_rows(const wq_plan *p, hipStream_t s, const float *w, const float *bias,
+                                 int8_t *Wq, float *sW, float *bias_out) {
+    const dim3 grid((unsigned)((p->Cout_pad / 16) * (p->Cin / 32))), block(256);
+    hipLaunchKernelGGL(k_quantize_weight_rows, grid, block, 0, s, w, Wq, sW, p->Cin, p->Cout,
+                       p->Cout_pad, ilog2(p->g / 32), p->kstep == 32 ? 5 : 6);
+    if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
+    hipLaunchKernelGGL(k_copy_bias, dim3((p->Cout_pad + 255) / 256), dim3(256), 0, s, bias, bias_out,
+                       p->Cout, p->Cout_pad);
+    return hipGetLastError();
 }
 
 hipError_t wq_launch_weight(const wq_plan *p, hipStream_t s, const float *w, const float *bias,

@@ -22,7 +22,7 @@ STATUS_NAMES = {0: "WQ_OK", 1: "WQ_ERR_INVALID_ARG", 2: "WQ_ERR_UNSUPPORTED",
 EXPORTS = ["wq_standard_transforms", "wq_plan_create", "wq_plan_destroy", "wq_plan_layout",
            "wq_weight_prepare", "wq_input_transform", "wq_contract_output", "wq_contract",
            "wq_output_transform", "wq_conv_forward",
-           "wq_direct_plan_create", "wq_direct_plan_destroy", "wq_direct_plan_layout",
+           "wq_direct_plan_create", "wq_linear_plan_create", "wq_direct_plan_destroy", "wq_direct_plan_layout",
            "wq_direct_weight_prepare", "wq_direct_quantize", "wq_direct_conv", "wq_direct_forward",
            "wq_conv_forward_debug", "wq_status_string"]
 
@@ -39,7 +39,7 @@ class Layout(ctypes.Structure):
 class DirectLayout(ctypes.Structure):
     _fields_ = ([(k, ctypes.c_int32) for k in
                  ("N", "H", "W", "Cin", "Cout", "group_size", "groups", "P", "Cout_pad", "kstep",
-                  "splits", "reserved")] +
+                  "splits", "taps")] +
                 [(k, ctypes.c_uint64) for k in
                  ("blob_bytes", "blob_Wq_off", "blob_sW_off", "blob_bias_off",
                   "ws_bytes", "ws_xq_off", "ws_sx_off", "ws_part_off")])
@@ -75,6 +75,7 @@ def lib() -> ctypes.CDLL:
         L.wq_conv_forward.argtypes = [vp, vp, vp, vp, sz, vp, sz, vp]
         L.wq_conv_forward_debug.argtypes = [vp, vp, vp, vp, sz, vp, sz, vp, vp, sz]
         L.wq_direct_plan_create.argtypes = [ctypes.POINTER(vp), ip, ip, ip, ip, ip, ip]
+        L.wq_linear_plan_create.argtypes = [ctypes.POINTER(vp), ip, ip, ip, ip]
         L.wq_direct_plan_destroy.argtypes = [vp]
         L.wq_direct_plan_layout.argtypes = [vp, ctypes.POINTER(DirectLayout)]
         L.wq_direct_weight_prepare.argtypes = [vp, vp, vp, vp, vp, sz]
@@ -296,10 +297,14 @@ class DirectPlan:
     """The group-wise quantized standard 3x3 convolution (the paper's runtime
     comparison point) for one layer shape.  Owns only the host-side plan object."""
 
-    def __init__(self, N, H, W, Cin, Cout, group_size):
+    def __init__(self, N, H, W, Cin, Cout, group_size, linear: bool = False):
         self._h = ctypes.c_void_p()
-        _check(lib().wq_direct_plan_create(ctypes.byref(self._h), N, H, W, Cin, Cout, group_size),
-               "wq_direct_plan_create")
+        if linear:   # N rows, H = W = 1: a group-wise quantized linear layer
+            _check(lib().wq_linear_plan_create(ctypes.byref(self._h), N * H * W, Cin, Cout, group_size),
+                   "wq_linear_plan_create")
+        else:
+            _check(lib().wq_direct_plan_create(ctypes.byref(self._h), N, H, W, Cin, Cout, group_size),
+                   "wq_direct_plan_create")
         self.layout = DirectLayout()
         _check(lib().wq_direct_plan_layout(self._h, ctypes.byref(self.layout)), "wq_direct_plan_layout")
 
@@ -323,16 +328,16 @@ class DirectPlan:
         return torch.empty((L.N, L.H, L.W, L.Cout), dtype=torch.float32, device=device)
 
     def blob_views(self, blob):
-        """(Wq [9][Cout_pad][Cin] int8, sW [9][groups][Cout_pad] fp32, bias [Cout_pad]) - the int8
-        tensor un-blocked (a pure index permutation)."""
+        """(Wq [taps][Cout_pad][Cin] int8, sW [taps][groups][Cout_pad] fp32, bias [Cout_pad]) - the
+        int8 tensor un-blocked (a pure index permutation)."""
         import torch
         L = self.layout
-        R, ks = L.Cout_pad, L.kstep
-        raw = blob[L.blob_Wq_off:L.blob_Wq_off + 9 * R * L.Cin].view(torch.int8)
-        Wq = raw.view(9, R // 16, L.Cin // ks, 4, 16, ks // 4).permute(0, 1, 4, 2, 3, 5) \
-            .reshape(9, R, L.Cin)
-        sW = blob[L.blob_sW_off:L.blob_sW_off + 9 * L.groups * R * 4].view(torch.float32) \
-            .view(9, L.groups, R)
+        R, ks, nt = L.Cout_pad, L.kstep, L.taps
+        raw = blob[L.blob_Wq_off:L.blob_Wq_off + nt * R * L.Cin].view(torch.int8)
+        Wq = raw.view(nt, R // 16, L.Cin // ks, 4, 16, ks // 4).permute(0, 1, 4, 2, 3, 5) \
+            .reshape(nt, R, L.Cin)
+        sW = blob[L.blob_sW_off:L.blob_sW_off + nt * L.groups * R * 4].view(torch.float32) \
+            .view(nt, L.groups, R)
         bias = blob[L.blob_bias_off:L.blob_bias_off + R * 4].view(torch.float32)
         return Wq, sW, bias
 
@@ -347,7 +352,7 @@ class DirectPlan:
     def weight_prepare(self, w, bias, blob, stream=None):
         import torch
         L = self.layout
-        wp = _dev_ptr(w, torch.float32, "w", L.Cout * L.Cin * 9)
+        wp = _dev_ptr(w, torch.float32, "w", L.Cout * L.Cin * L.taps)
         bp = None if bias is None else _dev_ptr(bias, torch.float32, "bias", L.Cout)
         _check(lib().wq_direct_weight_prepare(self._h, _stream_handle(stream), wp, bp,
                                               _dev_ptr(blob, torch.uint8, "blob"), blob.numel()),

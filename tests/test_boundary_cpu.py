@@ -163,3 +163,16 @@ def test_direct_plan_layout_and_argument_errors(wq):
     assert lib.wq_direct_quantize(h, None, fake, fake, 16) == 5          # workspace too small
     assert lib.wq_direct_conv(h, None, fake, 1 << 30, fake, 1 << 30, fake) == 4   # never prepared
     lib.wq_direct_plan_destroy(h)
+
+
+def test_linear_plan_layout_and_argument_errors(wq):
+    p = wq.DirectPlan(50, 1, 1, 128, 40, 64, linear=True)
+    L = p.layout
+    assert (L.P, L.taps, L.splits, L.groups, L.kstep) == (50, 1, 1, 2, 64)
+    assert L.blob_sW_off >= L.Cout_pad * 128 and L.ws_sx_off >= 50 * 128
+    lib = wq.lib()
+    h = ctypes.c_void_p()
+    assert lib.wq_linear_plan_create(ctypes.byref(h), 0, 128, 40, 64) == 1
+    assert lib.wq_linear_plan_create(ctypes.byref(h), 8, 100, 40, 64) == 1     # Cin % g
+    assert lib.wq_linear_plan_create(ctypes.byref(h), 8, 128, 40, 48) == 2     # group size
+    assert lib.wq_linear_plan_create(None, 8, 128, 40, 64) == 1

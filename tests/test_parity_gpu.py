@@ -231,7 +231,9 @@ def test_wide_layer_at_reduced_batch(wq, idx):
     import dataclasses
     d = workloads.make_layer_data(lay, N=4)
     d.layer = dataclasses.replace(lay, N=4)
-    assert wq.Plan(4, lay.H, lay.W, lay.Cin, lay.Cout, lay.m, lay.group_size).layout.k2_kernels == 2
+    import os
+    if "WQ_K2_PATH" not in os.environ:   # the library's own choice for a layer this wide
+        assert wq.Plan(4, lay.H, lay.W, lay.Cin, lay.Cout, lay.m, lay.group_size).layout.k2_kernels == 2
     check(wq, d, want_P=False)
 
 

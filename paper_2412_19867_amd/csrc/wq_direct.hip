@@ -116,7 +116,10 @@ __global__ __launch_bounds__(256, 2) void k_direct_conv(const DArgs a) {
     constexpr int KSTEP = K64 ? 64 : 32, KB = KSTEP / 4;
     constexpr int BLK = 16 * KSTEP;   // bytes of one K-step of a 16-row block
     constexpr int LPT = K64 ? 2 : 1;  // 16-byte loads per thread per K-step
-    constexpr int PD = 4;             // K-steps in flight
+#ifndef WQ_DIRECT_PD
+#define WQ_DIRECT_PD 4
+#endif
+    constexpr int PD = WQ_DIRECT_PD;   // K-steps in flight
     __shared__ __attribute__((aligned(16))) char opnd[2][8 * BLK];   // blocks 0-3 weights, 4-7 pixels
     __shared__ __attribute__((aligned(16))) float sc[2][128];        // 64 weight scales, 64 pixel scales
 

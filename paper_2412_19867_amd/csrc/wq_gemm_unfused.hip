@@ -9,7 +9,7 @@
 //                       256 threads copy four 16-row weight blocks and four
 //                       16-row activation blocks (already in MFMA operand
 //                       order) plus the 64+64 scales of the group into LDS,
-//                       double buffered, fed from a register ring that keeps four
+//                       double buffered, fed from a register ring that keeps two
 //                       K-steps in flight; every wave owns a 32x32 quarter
 //                       (2x2 int8 MFMA blocks, fresh int32 accumulators per
 //                       group) and dequantizes into fp32 at each group end.
@@ -103,7 +103,7 @@ __global__ __launch_bounds__(256, 2) void k_gemm_dequant(const GArgs a) {
     // s & 1 while step s+1 moves from its ring slot into the other buffer.  Every wave
     // issues the same number of loads per K-step and no load sits under a branch, so the
     // wait before the move leaves the newer K-steps outstanding.
-    constexpr int PD = 4;
+    constexpr int PD = 2;   // measured: 2, 4, 6, 8 K-steps in flight; 2 is as fast as any and starts sooner
     v4i pre[PD][LPT];
     float psc[PD];
     auto fetch = [&](int s, v4i (&dst)[LPT], float &dsc) {   // global -> registers for K-step s

@@ -11,7 +11,7 @@
 // channels; per K-step the 256 threads copy four 16-channel weight blocks (already in MFMA
 // operand order) and gather the 64 input pixels of the current tap - shifted by the tap's
 // offset, zero where the window leaves the image - into MFMA operand order in LDS, plus the
-// 64+64 scales of the group.  Four K-steps are in flight in a statically indexed register
+// 64+64 scales of the group.  Two K-steps are in flight in a statically indexed register
 // ring; every wave computes a 2x2 arrangement of 16x16 int8 MFMA blocks into fresh int32
 // accumulators per group and folds them into fp32 with the two scales.
 #include <float.h>
@@ -116,10 +116,7 @@ __global__ __launch_bounds__(256, 2) void k_direct_conv(const DArgs a) {
     constexpr int KSTEP = K64 ? 64 : 32, KB = KSTEP / 4;
     constexpr int BLK = 16 * KSTEP;   // bytes of one K-step of a 16-row block
     constexpr int LPT = K64 ? 2 : 1;  // 16-byte loads per thread per K-step
-#ifndef WQ_DIRECT_PD
-#define WQ_DIRECT_PD 4
-#endif
-    constexpr int PD = WQ_DIRECT_PD;   // K-steps in flight
+    constexpr int PD = 2;             // K-steps in flight (deeper rings measured no faster)
     __shared__ __attribute__((aligned(16))) char opnd[2][8 * BLK];   // blocks 0-3 weights, 4-7 pixels
     __shared__ __attribute__((aligned(16))) float sc[2][128];        // 64 weight scales, 64 pixel scales
 

@@ -191,8 +191,8 @@ wq_status_t wq_plan_create(wq_plan_t **out, int N, int H, int W, int Cin, int Co
     // beats the fused kernel; so it does for very wide layers and for groups of 128 and more,
     // where the fused kernel's register tiles re-read the operands too often.
     // WQ_K2_PATH=fused|split overrides.
-    p->two_kernel = (p->T_pad <= 512 && (Cin >= 512 || group_size == 32)) || Cin >= 1024 ||
-                    group_size >= 128;
+    p->two_kernel = (p->T_pad <= 512 && (Cin >= 512 || (group_size == 32 && Cin >= 128))) ||
+                    Cin >= 1024 || group_size >= 128;
     if (const char *e = std::getenv("WQ_K2_PATH")) {
         if (!std::strcmp(e, "fused")) p->two_kernel = false;
         if (!std::strcmp(e, "split")) p->two_kernel = true;

@@ -50,7 +50,9 @@ __global__ __launch_bounds__(256, 2) void k_gemm_dequant(const GArgs a) {
     constexpr int NB = OBW + TBW;                // blocks per stage: weights first, then activations
     constexpr int CPB = BLK / 16;                // 16-byte chunks per block
     constexpr int LPT = (NB * CPB + 255) / 256;  // 16-byte loads per thread per K-step
-    constexpr int WN = OBW / 2, NSW = OBW * 16, NSX = TBW * 16;   // waves along channels; scales per stage
+    constexpr int WN = TBW == 2 ? 4 : 2, WM = 4 / WN;   // waves along channels / along tiles
+    constexpr int BN = OBW / WN, BM = TBW / WM;         // 16x16 blocks per wave along channels / tiles
+    constexpr int NSW = OBW * 16, NSX = TBW * 16;       // scales per stage
     constexpr unsigned kInvalid = 1u << 31;      // an offset past the end of any buffer (all < 2 GiB): loads 0
     __shared__ __attribute__((aligned(16))) char opnd[2][NB * BLK];
     __shared__ __attribute__((aligned(16))) float sc[2][NSW + NSX];   // weight scales, then activation scales
@@ -125,13 +127,13 @@ __global__ __launch_bounds__(256, 2) void k_gemm_dequant(const GArgs a) {
         if (tid < NSW + NSX) sc[buf][tid] = ssc;
     };
 
-    v4i acc[2][2];
-    float4 Mc[2][2];
-    double Mt[2][2][4];
+    v4i acc[BN][BM];
+    float4 Mc[BN][BM];
+    double Mt[BN][BM][4];
 #pragma unroll
-    for (int no = 0; no < 2; ++no)
+    for (int no = 0; no < BN; ++no)
 #pragma unroll
-        for (int nt = 0; nt < 2; ++nt) {
+        for (int nt = 0; nt < BM; ++nt) {
             acc[no][nt] = v4i{0, 0, 0, 0};
             Mc[no][nt] = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
@@ -151,25 +153,32 @@ __global__ __launch_bounds__(256, 2) void k_gemm_dequant(const GArgs a) {
         if (s >= cps) break;
         const int buf = u & 1;   // PD is even, so s & 1 == u & 1
         fetch(min(s + PD, last), pre[u], psc[u]);   // slot u held step s, already in LDS
-        // operands of this wave's 2x2 blocks
-        v4i av[2], bv[2];
+        // operands of this wave's BN x BM blocks
+        v4i av[BN], bv[BM];
 #pragma unroll
-        for (int e = 0; e < 2; ++e) {
-            const char *pa = &opnd[buf][(2 * wn + e) * BLK + lane * KB];
-            const char *pb = &opnd[buf][(OBW + 2 * wm + e) * BLK + lane * KB];
+        for (int e = 0; e < BN; ++e) {
+            const char *pa = &opnd[buf][(BN * wn + e) * BLK + lane * KB];
             if constexpr (K64) {
                 av[e] = *reinterpret_cast<const v4i *>(pa);
+            } else {
+                const v2i ta = *reinterpret_cast<const v2i *>(pa);
+                av[e] = v4i{ta.x, ta.y, 0, 0};
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < BM; ++e) {
+            const char *pb = &opnd[buf][(OBW + BM * wm + e) * BLK + lane * KB];
+            if constexpr (K64) {
                 bv[e] = *reinterpret_cast<const v4i *>(pb);
             } else {
-                const v2i ta = *reinterpret_cast<const v2i *>(pa), tb = *reinterpret_cast<const v2i *>(pb);
-                av[e] = v4i{ta.x, ta.y, 0, 0};
+                const v2i tb = *reinterpret_cast<const v2i *>(pb);
                 bv[e] = v4i{tb.x, tb.y, 0, 0};
             }
         }
 #pragma unroll
-        for (int no = 0; no < 2; ++no)
+        for (int no = 0; no < BN; ++no)
 #pragma unroll
-            for (int nt = 0; nt < 2; ++nt) {
+            for (int nt = 0; nt < BM; ++nt) {
                 const v4i c0 = CPG1 ? v4i{0, 0, 0, 0} : acc[no][nt];
                 if constexpr (K64) {
                     acc[no][nt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(av[no], bv[nt], c0, 0, 0, 0);
@@ -181,11 +190,11 @@ __global__ __launch_bounds__(256, 2) void k_gemm_dequant(const GArgs a) {
             }
         if (CPG1 || ((s + 1) & cpg_mask) == 0) {   // last K-step of a group: dequantize
 #pragma unroll
-            for (int no = 0; no < 2; ++no) {
-                const v4f sw = *reinterpret_cast<const v4f *>(&sc[buf][(2 * wn + no) * 16 + 4 * q]);
+            for (int no = 0; no < BN; ++no) {
+                const v4f sw = *reinterpret_cast<const v4f *>(&sc[buf][(BN * wn + no) * 16 + 4 * q]);
 #pragma unroll
-                for (int nt = 0; nt < 2; ++nt) {
-                    const float sx = sc[buf][NSW + (2 * wm + nt) * 16 + l16];
+                for (int nt = 0; nt < BM; ++nt) {
+                    const float sx = sc[buf][NSW + (BM * wm + nt) * 16 + l16];
                     Mc[no][nt].x = __builtin_fmaf((float)acc[no][nt][0], sw.x * sx, Mc[no][nt].x);
                     Mc[no][nt].y = __builtin_fmaf((float)acc[no][nt][1], sw.y * sx, Mc[no][nt].y);
                     Mc[no][nt].z = __builtin_fmaf((float)acc[no][nt][2], sw.z * sx, Mc[no][nt].z);
@@ -196,9 +205,9 @@ __global__ __launch_bounds__(256, 2) void k_gemm_dequant(const GArgs a) {
             if (WIDE && ++in_chunk == 4) {   // fp64 totals of 4-group fp32 chunks (long reductions)
                 in_chunk = 0;
 #pragma unroll
-                for (int no = 0; no < 2; ++no)
+                for (int no = 0; no < BN; ++no)
 #pragma unroll
-                    for (int nt = 0; nt < 2; ++nt) {
+                    for (int nt = 0; nt < BM; ++nt) {
                         Mt[no][nt][0] += (double)Mc[no][nt].x;
                         Mt[no][nt][1] += (double)Mc[no][nt].y;
                         Mt[no][nt][2] += (double)Mc[no][nt].z;
@@ -217,14 +226,14 @@ __global__ __launch_bounds__(256, 2) void k_gemm_dequant(const GArgs a) {
     // store M [tile][tap][Cout_pad] (a tile's taps together: the output transform reads them
     // from one contiguous region); the lane holds channels 4q..4q+3 of tile l16 in each block
 #pragma unroll
-    for (int no = 0; no < 2; ++no)
+    for (int no = 0; no < BN; ++no)
 #pragma unroll
-        for (int nt = 0; nt < 2; ++nt) {
+        for (int nt = 0; nt < BM; ++nt) {
             float4 Mv = Mc[no][nt];
             if constexpr (WIDE)
                 Mv = make_float4((float)(Mt[no][nt][0] + (double)Mv.x), (float)(Mt[no][nt][1] + (double)Mv.y),
                                  (float)(Mt[no][nt][2] + (double)Mv.z), (float)(Mt[no][nt][3] + (double)Mv.w));
-            const int tau = (tb0 + 2 * wm + nt) * 16 + l16, o = (ob0 + 2 * wn + no) * 16 + 4 * q;
+            const int tau = (tb0 + BM * wm + nt) * 16 + l16, o = (ob0 + BN * wn + no) * 16 + 4 * q;
             if (tau < T_pad && o < Cout_pad)
                 __builtin_amdgcn_raw_buffer_store_b128(
                     __builtin_bit_cast(v4i, v4f{Mv.x, Mv.y, Mv.z, Mv.w}), rM,
@@ -292,8 +301,15 @@ __global__ __launch_bounds__(64 * M) void k_output_transform(const OArgs a) {
 }
 
 template <bool K64, bool CPG1>
-void launch_gemm(const GArgs &g, hipStream_t s, bool wide, bool narrow) {
+void launch_gemm(const GArgs &g, hipStream_t s, bool wide, bool narrow, bool big) {
     const unsigned taps = (unsigned)g.n2;
+    if constexpr (K64 && !CPG1) {
+        if (big && !wide) {
+            const dim3 grid((g.Cout_pad + 127) / 128, (g.T_pad + 127) / 128, taps);
+            hipLaunchKernelGGL((k_gemm_dequant<true, false, false, 8>), grid, dim3(256), 0, s, g);
+            return;
+        }
+    }
     if (narrow) {
         const dim3 grid((g.Cout_pad + 127) / 128, g.T_pad / 32, taps);
         if (wide)
@@ -335,9 +351,15 @@ hipError_t wq_launch_contract_unfused(const wq_plan *p, hipStream_t s, const int
         if (!std::strcmp(e, "32")) narrow = true;
         if (!std::strcmp(e, "64")) narrow = false;
     }
-    if (!k64) launch_gemm<false, true>(g, s, wide, narrow);
-    else if (cpg1) launch_gemm<true, true>(g, s, wide, narrow);
-    else launch_gemm<true, false>(g, s, wide, narrow);
+    // 128x128 tiles: groups of 128 and more on layers with at least 1024 tiles and 256 channels
+    bool big = p->g >= 128 && p->T_pad >= 1024 && p->Cout_pad >= 256;
+    if (const char *e = std::getenv("WQ_GEMM_TILE")) {
+        if (!std::strcmp(e, "128")) big = true;
+        if (!std::strcmp(e, "32") || !std::strcmp(e, "64")) big = false;
+    }
+    if (!k64) launch_gemm<false, true>(g, s, wide, narrow, big);
+    else if (cpg1) launch_gemm<true, true>(g, s, wide, narrow, big);
+    else launch_gemm<true, false>(g, s, wide, narrow, big);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     }

@@ -158,8 +158,8 @@ wq_status_t wq_conv_forward_debug(const wq_plan_t *plan, void *stream, const flo
  * Conventions as above: caller-owned device memory, calls enqueue on `stream`
  * and never synchronise, every argument is checked on the host.  Errors:
  * non-positive sizes, NULL pointers, Cin not a multiple of group_size ->
- * INVALID_ARG; group_size not in {32,64,128,256,512} or a tensor of 2 GiB or
- * more -> UNSUPPORTED; a buffer smaller than the layout says -> WORKSPACE;
+ * INVALID_ARG; group_size not in {32,64,128,256,512}, a tensor of 2 GiB or
+ * more, or more than 4193280 pixels (rows) -> UNSUPPORTED; a buffer smaller than the layout says -> WORKSPACE;
  * conv before weight_prepare -> NOT_PREPARED. */
 typedef struct wq_direct_plan wq_direct_plan_t;
 

@@ -373,6 +373,7 @@ static wq_status_t make_plan(wq_direct_plan_t **out, int N, int H, int W, int Ci
     if (P * Cin * 4 > lim || P * Cout * 4 > lim || taps * Cp * Cin > lim ||
         taps * Cp * (Cin / group_size) * 4 > lim)
         return WQ_ERR_UNSUPPORTED;
+    if ((P + 63) / 64 > 65535) return WQ_ERR_UNSUPPORTED;   // pixel tiles are the grid's y dimension
     wq_direct_plan *p = new (std::nothrow) wq_direct_plan();
     if (!p) return WQ_ERR_INVALID_ARG;
     p->N = N; p->H = H; p->W = W; p->Cin = Cin; p->Cout = Cout; p->g = group_size;

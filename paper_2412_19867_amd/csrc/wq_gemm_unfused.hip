@@ -262,7 +262,7 @@ __global__ __launch_bounds__(64 * M) void k_output_transform(const OArgs a) {
     __shared__ __attribute__((aligned(16))) float Ms[n2][64];
     const int tid = threadIdx.x, ol = tid & 63;
     const int b = __builtin_amdgcn_readfirstlane(tid >> 6);   // output column of this wave
-    const int o0 = blockIdx.x * 64, tau = blockIdx.y;
+    const int o0 = blockIdx.y * 64, tau = blockIdx.x;
     const float *src = a.Mbuf + (size_t)tau * n2 * a.Cout_pad + o0;   // M [tile][tap][Cout_pad]
     for (int idx = tid; idx < n2 * 16; idx += 64 * M) {
         const int t = idx >> 4, c4 = (idx & 15) * 4;
@@ -369,7 +369,7 @@ hipError_t wq_launch_contract_unfused(const wq_plan *p, hipStream_t s, const int
     o.xf = p->xf; o.Mbuf = Mbuf; o.bias = bias; o.y = y;
     o.H = p->H; o.W = p->W; o.Cout = p->Cout; o.TH = p->TH; o.TW = p->TW; o.T = p->T;
     o.T_pad = p->T_pad; o.Cout_pad = p->Cout_pad;
-    const dim3 ogrid((p->Cout + 63) / 64, p->T);
+    const dim3 ogrid(p->T, (p->Cout + 63) / 64);   // tiles along x: y holds 65535 at most
     switch (p->m) {
         case 2: launch_out<2>(o, ogrid, s, p->sparse_at); break;
         case 4: launch_out<4>(o, ogrid, s, p->sparse_at); break;

@@ -176,3 +176,12 @@ def test_linear_plan_layout_and_argument_errors(wq):
     assert lib.wq_linear_plan_create(ctypes.byref(h), 8, 100, 40, 64) == 1     # Cin % g
     assert lib.wq_linear_plan_create(ctypes.byref(h), 8, 128, 40, 48) == 2     # group size
     assert lib.wq_linear_plan_create(None, 8, 128, 40, 64) == 1
+
+
+def test_direct_plan_refuses_more_pixels_than_the_launch_grid_holds(wq):
+    lib = wq.lib()
+    h = ctypes.c_void_p()
+    # 64 pixels per workgroup along the grid's y dimension, which holds 65535 workgroups.
+    assert lib.wq_direct_plan_create(ctypes.byref(h), 1, 2048, 2048, 32, 32, 32) == 2   # WQ_ERR_UNSUPPORTED
+    assert lib.wq_direct_plan_create(ctypes.byref(h), 1, 2047, 2048, 32, 32, 32) == 0
+    lib.wq_direct_plan_destroy(h)

@@ -108,3 +108,9 @@ def test_direct_random_small_shapes(wq, case):
     seed, N, H, W, Cin, Cout, g = case
     d = workloads.small_layer(seed, N, H, W, Cin, Cout, 4, g)
     check_direct(wq, d.x, d.w, d.bias, g, "random%d" % seed)
+
+
+def test_direct_largest_pixel_count(wq):
+    """Just under the largest pixel count a plan takes (65535 pixel tiles of 64)."""
+    d = workloads.small_layer(78, 1, 2047, 2048, 32, 32, 4, 32)
+    check_direct(wq, d.x, d.w, d.bias, 32, "largest")

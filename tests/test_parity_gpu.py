@@ -255,3 +255,15 @@ def test_random_small_shapes(wq, case):
     seed, N, H, W, Cin, Cout, m, g, scaled = case
     d = workloads.small_layer(seed, N, H, W, Cin, Cout, m, g, row_scales=scaled)
     check(wq, d)
+
+
+def test_largest_supported_input(wq):
+    """An input of exactly 1 GiB (the plan's limit) with a 1 GiB int8 operand tensor: every
+    32-bit offset of the transform and contraction kernels is exercised near its top."""
+    d = workloads.small_layer(77, 8, 512, 512, 128, 32, 2, 32)
+    assert d.x.nbytes == 1 << 30
+    lib = wq.lib()
+    import ctypes
+    h = ctypes.c_void_p()
+    assert lib.wq_plan_create(ctypes.byref(h), 8, 512, 513, 128, 32, 2, 32, None, None, None) == 2   # one column more
+    check(wq, d, want_P=False)

@@ -267,3 +267,13 @@ def test_largest_supported_input(wq):
     h = ctypes.c_void_p()
     assert lib.wq_plan_create(ctypes.byref(h), 8, 512, 513, 128, 32, 2, 32, None, None, None) == 2   # one column more
     check(wq, d, want_P=False)
+
+
+def test_two_kernel_form_with_more_than_65535_tiles(wq):
+    """Groups of 128 take the GEMM + output-transform kernels; 100352 tiles is more than one
+    grid dimension other than x holds."""
+    d = workloads.small_layer(79, 32, 112, 112, 128, 32, 2, 128)
+    import os
+    if "WQ_K2_PATH" not in os.environ:
+        assert wq.Plan(32, 112, 112, 128, 32, 2, 128).layout.k2_kernels == 2
+    check(wq, d, want_P=False)

@@ -18,13 +18,14 @@
 //   phase C  every lane quantizes its values as rint(v*r) (rounded product,
 //            then round-half-even via the 1.5*2^23 add); the codes go through LDS
 //            and leave as 16-byte stores that fill whole cache lines.
-// The input kernel additionally splits the n tap rows in two halves over
-// blockIdx.y: B^T d only has to be formed for the workgroup's rows, so the
-// split costs nothing but re-reading the tile through L1, and it halves the
-// registers and the length of the per-wave instruction stream.
+// The input kernel can additionally split the n tap rows over blockIdx.y:
+// B^T d only has to be formed for the workgroup's rows, so the split costs
+// nothing but re-reading the tile through L1, and it cuts the registers and
+// the length of the per-wave instruction stream (see tap_rows_per_wg).
 // The arithmetic order is part of the library's contract: the int8 codes and
 // scales are reproducible bit for bit from the definition in include/wq.h.
 #include <float.h>
+#include <stdlib.h>
 
 #include "wq_internal.h"
 
@@ -167,17 +168,26 @@ __device__ __forceinline__ void quantize_and_store(const float2 (&vals)[NT], uin
 }
 
 // ---------------------------------------------------------------- stage 1
-// tap rows per workgroup of the input kernel: half of them (measured best of n, n/2, n/4, 1)
-template <int M>
-constexpr int tap_rows_per_wg() { return (M + 2) / 2; }
+// Tap rows per workgroup of the input kernel.  A workgroup that forms all n rows reads its
+// tiles once and has the longest instruction stream per wave; splitting the rows over
+// blockIdx.y re-reads the tiles through L1/L2 but shortens the stream and multiplies the
+// waves.  Measured over layers from 32 to 20480 waves (counted with all rows in one
+// workgroup): big layers want all rows together, mid-sized ones halves, small ones two
+// rows (one row only when the layer is a handful of waves).
+inline int tap_rows_per_wg(int n, long waves_all_rows) {
+    if (waves_all_rows >= 1536) return n;
+    if (n == 8 || waves_all_rows >= 1024) return n / 2;
+    if (waves_all_rows >= 128) return 2;
+    return 1;
+}
 
-template <int M, int I0, bool SPARSE>
+template <int M, int TR, int I0, bool SPARSE>
 __device__ __forceinline__ void input_body(const wq_xf &xf, const float *__restrict__ x,
                                            int8_t *__restrict__ Xq, float *__restrict__ sX, int H,
                                            int W, int Cin, int TH, int TW, int T, int T_pad,
                                            int log2k, int kstep_log2, unsigned x_bytes,
                                            uint4 (*amax_s)[16], float (*r_s)[16], char *codes_s) {
-    constexpr int n = M + 2, TR = tap_rows_per_wg<M>(), NT = TR * n;
+    constexpr int n = M + 2, NT = TR * n;
     using Pat = wq_pattern<M>;
     const int tid = threadIdx.x, row = tid >> 4, l16 = tid & 15;
     const int k = 1 << log2k;
@@ -266,28 +276,32 @@ __device__ __forceinline__ void input_body(const wq_xf &xf, const float *__restr
                            (long)RB * groups * 16, 16);
 }
 
-template <int M, bool SPARSE>
+template <int M, int TR, bool SPARSE>
 __global__ __launch_bounds__(256) void k_input_transform(wq_xf xf, const float *__restrict__ x,
                                                          int8_t *__restrict__ Xq,
                                                          float *__restrict__ sX, int H, int W,
                                                          int Cin, int TH, int TW, int T, int T_pad,
                                                          int log2k, int kstep_log2,
                                                          unsigned x_bytes) {
-    constexpr int n = M + 2, TR = tap_rows_per_wg<M>();
+    constexpr int n = M + 2;
     __shared__ uint4 amax_s[TR * n][16];
     __shared__ float r_s[TR * n][16];
     __shared__ __attribute__((aligned(16))) char codes_s[TR * n * kTapStride];
 #define WQ_BODY(I0)                                                                            \
-    input_body<M, (I0), SPARSE>(xf, x, Xq, sX, H, W, Cin, TH, TW, T, T_pad, log2k, kstep_log2, \
+    input_body<M, TR, (I0), SPARSE>(xf, x, Xq, sX, H, W, Cin, TH, TW, T, T_pad, log2k, kstep_log2, \
                                 x_bytes, amax_s, r_s, codes_s)
     // uniform branch: which block of TR tap rows this workgroup forms
     constexpr int NY = n / TR;
-    static_assert(NY * TR == n && NY <= 4, "unsupported tap-row split");
+    static_assert(NY * TR == n && NY <= 8, "unsupported tap-row split");
     const int yb = blockIdx.y;
     if (yb == 0) WQ_BODY(0);
     if constexpr (NY > 1) { if (yb == 1) WQ_BODY(TR); }
     if constexpr (NY > 2) { if (yb == 2) WQ_BODY(2 * TR); }
     if constexpr (NY > 3) { if (yb == 3) WQ_BODY(3 * TR); }
+    if constexpr (NY > 4) { if (yb == 4) WQ_BODY(4 * TR); }
+    if constexpr (NY > 5) { if (yb == 5) WQ_BODY(5 * TR); }
+    if constexpr (NY > 6) { if (yb == 6) WQ_BODY(6 * TR); }
+    if constexpr (NY > 7) { if (yb == 7) WQ_BODY(7 * TR); }
 #undef WQ_BODY
 }
 
@@ -420,19 +434,29 @@ int ilog2(int v) {
     return l;
 }
 
-template <int M>
-hipError_t launch_input_m(const wq_plan *p, hipStream_t s, const float *x, int8_t *Xq, float *sX) {
-    const dim3 grid((unsigned)((p->T_pad / 16) * (p->Cin / 32)), (M + 2) / tap_rows_per_wg<M>()),
-        block(256);
+template <int M, int TR>
+hipError_t launch_input_rows(const wq_plan *p, hipStream_t s, const float *x, int8_t *Xq, float *sX) {
+    const dim3 grid((unsigned)((p->T_pad / 16) * (p->Cin / 32)), (M + 2) / TR), block(256);
     const int log2k = ilog2(p->g / 32), kstep_log2 = p->kstep == 32 ? 5 : 6;
     const unsigned x_bytes = (unsigned)((size_t)p->N * p->H * p->W * p->Cin * 4);
     if (p->sparse_bt)
-        hipLaunchKernelGGL((k_input_transform<M, true>), grid, block, 0, s, p->xf, x, Xq, sX, p->H,
+        hipLaunchKernelGGL((k_input_transform<M, TR, true>), grid, block, 0, s, p->xf, x, Xq, sX, p->H,
                            p->W, p->Cin, p->TH, p->TW, p->T, p->T_pad, log2k, kstep_log2, x_bytes);
     else
-        hipLaunchKernelGGL((k_input_transform<M, false>), grid, block, 0, s, p->xf, x, Xq, sX, p->H,
+        hipLaunchKernelGGL((k_input_transform<M, TR, false>), grid, block, 0, s, p->xf, x, Xq, sX, p->H,
                            p->W, p->Cin, p->TH, p->TW, p->T, p->T_pad, log2k, kstep_log2, x_bytes);
     return hipGetLastError();
+}
+
+template <int M>
+hipError_t launch_input_m(const wq_plan *p, hipStream_t s, const float *x, int8_t *Xq, float *sX) {
+    constexpr int n = M + 2;
+    int tr = tap_rows_per_wg(n, (long)(p->T_pad / 16) * (p->Cin / 32) * 4);
+    if (const char *e = getenv("WQ_K1_ROWS")) tr = atoi(e);   // for sweeps: n, n/2, 2 or 1
+    if (tr == n) return launch_input_rows<M, n>(p, s, x, Xq, sX);
+    if (tr == 1) return launch_input_rows<M, 1>(p, s, x, Xq, sX);
+    if (tr == 2) return launch_input_rows<M, 2>(p, s, x, Xq, sX);
+    return launch_input_rows<M, n / 2>(p, s, x, Xq, sX);
 }
 
 template <int M>

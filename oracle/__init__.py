@@ -178,13 +178,15 @@ def quantize_pixels(x, g: int):
     return xq, sx
 
 
-def quantize_filters(w, g: int):
-    """w [Cout][Cin][3][3] fp32 -> (wq [9][Cout][Cin] int8, sw [9][Cin/g][Cout] fp32)."""
+def quantize_filters(w, g: int, bits: int = 8):
+    """w [Cout][Cin][3][3] fp32 -> (wq [9][Cout][Cin] int8, sw [9][Cin/g][Cout] fp32);
+    bits = 4 gives codes in [-7, 7] (W4A8)."""
+    assert bits in (4, 8)
     w = _f32(w)
     Cout, Cin = w.shape[:2]
     wq = np.empty((9, Cout, Cin), dtype=np.int8)
     sw = np.empty((9, Cin // g, Cout), dtype=np.float32)
-    _load().oracle_quantize_filters(_p(w), Cin, Cout, g, _p(wq), _p(sw))
+    _load().oracle_quantize_filters_bits(_p(w), Cin, Cout, g, bits, _p(wq), _p(sw))
     return wq, sw
 
 
@@ -202,34 +204,46 @@ def direct_qconv(xq, sx, wq, sw, bias, N: int, H: int, W: int, g: int):
     return y64, y32
 
 
-def direct_pipeline(x, w, bias, g: int) -> dict:
+def direct_pipeline(x, w, bias, g: int, weight_bits: int = 8) -> dict:
     """The whole group-wise quantized standard convolution."""
     x = _f32(x)
     N, H, W, _ = x.shape
     xq, sx = quantize_pixels(x, g)
-    wq, sw = quantize_filters(w, g)
+    wq, sw = quantize_filters(w, g, weight_bits)
     y64, y32 = direct_qconv(xq, sx, wq, sw, bias, N, H, W, g)
     return dict(xq=xq, sx=sx, wq=wq, sw=sw, y64=y64, y=y32)
 
 
 # ---- group-wise quantized linear layer (the 1-tap case of the same quantized GEMM)
-def quantize_weight_rows(w, g: int):
-    """w [Cout][Cin] fp32 -> (wq [Cout][Cin] int8, sw [Cin/g][Cout] fp32)."""
+def quantize_weight_rows(w, g: int, bits: int = 8):
+    """w [Cout][Cin] fp32 -> (wq [Cout][Cin] int8, sw [Cin/g][Cout] fp32);
+    bits = 4 gives codes in [-7, 7] (W4A8)."""
+    assert bits in (4, 8)
     w = _f32(w)
     Cout, Cin = w.shape
     wq = np.empty((Cout, Cin), dtype=np.int8)
     sw = np.empty((Cin // g, Cout), dtype=np.float32)
-    _load().oracle_quantize_weight_rows(_p(w), Cin, Cout, g, _p(wq), _p(sw))
+    _load().oracle_quantize_weight_rows_bits(_p(w), Cin, Cout, g, bits, _p(wq), _p(sw))
     return wq, sw
 
 
-def linear_pipeline(x, w, bias, g: int) -> dict:
+def quantize_group_bits(v, bits: int):
+    """One group through the `bits`-wide quantizer -> (codes int8, scale)."""
+    v = _f32(v).ravel()
+    q = np.empty(v.size, dtype=np.int8)
+    L = _load()
+    L.oracle_quantize_group_bits.restype = ctypes.c_float
+    s = L.oracle_quantize_group_bits(_p(v), v.size, bits, _p(q))
+    return q, np.float32(s)
+
+
+def linear_pipeline(x, w, bias, g: int, weight_bits: int = 8) -> dict:
     """x [R][Cin], w [Cout][Cin]: quantize both group-wise, multiply, rescale per group."""
     x, w = _f32(x), _f32(w)
     R, Cin = x.shape
     Cout = w.shape[0]
     xq, sx = quantize_pixels(x, g)
-    wq, sw = quantize_weight_rows(w, g)
+    wq, sw = quantize_weight_rows(w, g, weight_bits)
     b = None if bias is None else _f32(bias)
     y64 = np.empty((R, Cout), dtype=np.float64)
     y32 = np.empty((R, Cout), dtype=np.float32)

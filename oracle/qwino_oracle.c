@@ -164,34 +164,48 @@ void oracle_winograd_f64(const float *x, const float *w, const float *bias,
 }
 
 /* ------------------------------------------------------- the quantizer */
-/* Uniform symmetric int8 quantizer of one group: `count` values at stride
- * `vs` -> `count` codes at stride `qs`; returns the group's scale. */
-static float quantize_group(const float *v, size_t vs, int count, int8_t *q, size_t qs)
+/* Uniform symmetric quantizer of one group with codes in [-qmax, qmax]
+ * (qmax = 127 for 8 bits, 7 for 4 bits): `count` values at stride `vs` ->
+ * `count` codes at stride `qs`; returns the group's scale a/qmax. */
+static float quantize_group_q(const float *v, size_t vs, int count, int8_t *q, size_t qs, float qmax)
 {
     float a = 0.0f;
     for (int k = 0; k < count; ++k) {
         float t = fabsf(v[k * vs]);
         if (t > a) a = t;
     }
-    if (!(a >= 127.0f * FLT_MIN)) {
+    if (!(a >= qmax * FLT_MIN)) {
         for (int k = 0; k < count; ++k) q[k * qs] = 0;
         return 0.0f;
     }
-    const float s = a / 127.0f;
-    const float r = 127.0f / a;
+    const float s = a / qmax;
+    const float r = qmax / a;
     for (int k = 0; k < count; ++k) {
         float z = rintf(v[k * vs] * r);
-        if (z > 127.0f) z = 127.0f;
-        if (z < -127.0f) z = -127.0f;
+        if (z > qmax) z = qmax;
+        if (z < -qmax) z = -qmax;
         q[k * qs] = (int8_t)z;
     }
     return s;
 }
 
+static float quantize_group(const float *v, size_t vs, int count, int8_t *q, size_t qs)
+{
+    return quantize_group_q(v, vs, count, q, qs, 127.0f);
+}
+
+/* largest code of a `bits`-wide symmetric quantizer */
+static float qmax_of(int bits) { return (float)((1 << (bits - 1)) - 1); }
+
 /* exported for the quantizer's own tests */
 float oracle_quantize_group(const float *v, int count, int8_t *q)
 {
     return quantize_group(v, 1, count, q, 1);
+}
+
+float oracle_quantize_group_bits(const float *v, int count, int bits, int8_t *q)
+{
+    return quantize_group_q(v, 1, count, q, 1, qmax_of(bits));
 }
 
 /* -------------------------------------------------- stage 4 (offline) */
@@ -371,15 +385,24 @@ void oracle_quantize_pixels(const float *x, long P, int Cin, int g, int8_t *xq, 
                                                  xq + (size_t)p * Cin + (size_t)gi * g, 1);
 }
 
-void oracle_quantize_filters(const float *w, int Cin, int Cout, int g, int8_t *wq, float *sw)
+/* `bits` = width of the weight codes: 8 (W8A8) or 4 (the W4A8 rows of the paper's tables:
+ * the same symmetric abs-max quantizer with codes in [-7, 7]; activations stay 8-bit). */
+void oracle_quantize_filters_bits(const float *w, int Cin, int Cout, int g, int bits, int8_t *wq,
+                                  float *sw)
 {
     const int groups = Cin / g;
+    const float qmax = qmax_of(bits);
     for (int t = 0; t < 9; ++t)
         for (int o = 0; o < Cout; ++o)
             for (int gi = 0; gi < groups; ++gi)
                 sw[((size_t)t * groups + gi) * Cout + o] =
-                    quantize_group(w + ((size_t)o * Cin + (size_t)gi * g) * 9 + t, 9, g,
-                                   wq + ((size_t)t * Cout + o) * Cin + (size_t)gi * g, 1);
+                    quantize_group_q(w + ((size_t)o * Cin + (size_t)gi * g) * 9 + t, 9, g,
+                                     wq + ((size_t)t * Cout + o) * Cin + (size_t)gi * g, 1, qmax);
+}
+
+void oracle_quantize_filters(const float *w, int Cin, int Cout, int g, int8_t *wq, float *sw)
+{
+    oracle_quantize_filters_bits(w, Cin, Cout, g, 8, wq, sw);
 }
 
 /* y64 and y32 may each be NULL. */
@@ -428,13 +451,21 @@ void oracle_direct_qconv(const int8_t *xq, const float *sx, const int8_t *wq, co
  * (output row, group):  y[r][o] = bias[o] + sum_G P * sx[r][G] * sw[G][o].
  * Layouts: wq [Cout][Cin] int8, sw [Cin/g][Cout] fp32.
  * ====================================================================== */
-void oracle_quantize_weight_rows(const float *w, int Cin, int Cout, int g, int8_t *wq, float *sw)
+void oracle_quantize_weight_rows_bits(const float *w, int Cin, int Cout, int g, int bits,
+                                      int8_t *wq, float *sw)
 {
     const int groups = Cin / g;
+    const float qmax = qmax_of(bits);
     for (int o = 0; o < Cout; ++o)
         for (int gi = 0; gi < groups; ++gi)
-            sw[(size_t)gi * Cout + o] = quantize_group(w + (size_t)o * Cin + (size_t)gi * g, 1, g,
-                                                       wq + (size_t)o * Cin + (size_t)gi * g, 1);
+            sw[(size_t)gi * Cout + o] =
+                quantize_group_q(w + (size_t)o * Cin + (size_t)gi * g, 1, g,
+                                 wq + (size_t)o * Cin + (size_t)gi * g, 1, qmax);
+}
+
+void oracle_quantize_weight_rows(const float *w, int Cin, int Cout, int g, int8_t *wq, float *sw)
+{
+    oracle_quantize_weight_rows_bits(w, Cin, Cout, g, 8, wq, sw);
 }
 
 /* y64 and y32 may each be NULL. */

@@ -305,9 +305,26 @@ def main():
     lp.weight_prepare(torch.randn(lin_C, lin_C, device="cuda") * 0.02, None, lblob)
     lq_us = kernel_us(lambda: lp.quantize(lx, lws))
     lc_us = kernel_us(lambda: lp.conv(lws, lblob, ly))
+    # the same layer with 4-bit weight codes (W4A8), and a decode-sized batch of 16 rows against a
+    # 5120 x 5120 weight matrix, where the weights are the traffic
+    lp4 = wq.DirectPlan(lin_R, 1, 1, lin_C, lin_C, lin_g, linear=True, weight_bits=4)
+    lblob4 = lp4.alloc_blob()
+    lp4.weight_prepare(torch.randn(lin_C, lin_C, device="cuda") * 0.02, None, lblob4)
+    lc4_us = kernel_us(lambda: lp4.conv(lws, lblob4, ly))
+    sm_R, sm_C = 16, 5120
+    small = {}
+    for bits in (8, 4):
+        sp = wq.DirectPlan(sm_R, 1, 1, sm_C, sm_C, lin_g, linear=True, weight_bits=bits)
+        sblob, sws, sy = sp.alloc_blob(), sp.alloc_workspace(), sp.alloc_output()
+        sp.weight_prepare(torch.randn(sm_C, sm_C, device="cuda") * 0.02, None, sblob)
+        sp.quantize(torch.randn(sm_R, sm_C, device="cuda"), sws)
+        small[f"w{bits}a8_gemm_us"] = round(kernel_us(lambda: sp.conv(sws, sblob, sy)), 2)
     linear = dict(shape=f"{lin_R}x{lin_C}->{lin_C}, g={lin_g}", quantize_us=round(lq_us, 2),
                   gemm_us=round(lc_us, 2),
-                  int8_tops=round(2 * lin_R * lin_C * lin_C / ((lq_us + lc_us) * 1e-6) / 1e12, 1))
+                  int8_tops=round(2 * lin_R * lin_C * lin_C / ((lq_us + lc_us) * 1e-6) / 1e12, 1),
+                  w4a8_gemm_us=round(lc4_us, 2),
+                  w4a8_tops=round(2 * lin_R * lin_C * lin_C / ((lq_us + lc4_us) * 1e-6) / 1e12, 1),
+                  small_batch=dict(shape=f"{sm_R}x{sm_C}->{sm_C}, g={lin_g}", **small))
 
     cpu_baseline = None
     if not args.no_cpu_baseline and args.config != 6:

@@ -165,8 +165,11 @@ typedef struct wq_direct_plan wq_direct_plan_t;
 
 typedef struct {
     int32_t N, H, W, Cin, Cout, group_size, groups, P, Cout_pad, kstep;
-    int32_t splits, taps; /* splits: workgroups sharing the 9 taps of an output tile (1, 3 or 9);
+    int32_t splits, taps; /* splits: workgroups sharing the reduction of an output tile: the 9 taps
+                             (1, 3 or 9) or, for a linear layer, its groups (a power of two up to 16);
                              taps: 9 for the 3x3 convolution, 1 for a linear layer */
+    int32_t weight_bits;  /* 8, or 4 (W4A8) */
+    int32_t reserved;     /* 0 */
     uint64_t blob_bytes, blob_Wq_off, blob_sW_off, blob_bias_off;
     uint64_t ws_bytes, ws_xq_off, ws_sx_off, ws_part_off;
 } wq_direct_layout_t;
@@ -180,6 +183,19 @@ wq_status_t wq_direct_plan_create(wq_direct_plan_t **out, int N, int H, int W, i
  * use wq_direct_weight_prepare (w_dev is then [Cout][Cin]), wq_direct_quantize,
  * wq_direct_conv and wq_direct_forward with N*H*W = R; the layout has taps = 1. */
 wq_status_t wq_linear_plan_create(wq_direct_plan_t **out, int R, int Cin, int Cout, int group_size);
+/* W4A8 (the 4/8-bit rows of the paper's result tables, which apply to standard convolutions
+ * and linear layers): the same two plans with weight codes `weight_bits` wide, 8 or 4 (anything
+ * else -> UNSUPPORTED).  4-bit codes come from the same symmetric abs-max quantizer with codes
+ * in [-7, 7] and scale max|w|/7 per (tap, output channel, group); activations stay int8 with
+ * dynamic scales.  The blob then holds two codes per byte in the same blocked order: each
+ * aligned 16-byte piece d0 d1 d2 d3 (little-endian 32-bit words) of the int8 layout becomes
+ * the 8 bytes p0 p1 at half its offset, byte j of p0 carrying byte j of d0 in its low nibble and
+ * byte j of d1 in its high nibble (two's complement), p1 likewise from d2 and d3; Wq takes
+ * taps*Cout_pad*Cin/2 bytes.  Scales, bias, workspace and every other call are unchanged. */
+wq_status_t wq_direct_plan_create_bits(wq_direct_plan_t **out, int N, int H, int W, int Cin, int Cout,
+                                       int group_size, int weight_bits);
+wq_status_t wq_linear_plan_create_bits(wq_direct_plan_t **out, int R, int Cin, int Cout, int group_size,
+                                       int weight_bits);
 wq_status_t wq_direct_plan_destroy(wq_direct_plan_t *plan);
 wq_status_t wq_direct_plan_layout(const wq_direct_plan_t *plan, wq_direct_layout_t *out);
 

@@ -26,6 +26,7 @@ struct wq_direct_plan {
     wq_plan w;   // the offline weight stage as F(1,3): m = 1, n = 3, G = identity
     int N, H, W, Cin, Cout, g, groups, P, Cout_pad, kstep;
     int taps;     // 9 = 3x3 convolution, 1 = linear layer (every row is its own "image")
+    int wbits;    // width of the weight codes: 8, or 4 (W4A8: two codes per byte)
     int splits;   // the 9 filter taps are shared out over this many workgroups per output tile (1, 3 or 9)
     wq_direct_layout_t lay;
     std::atomic<int> prepared;
@@ -111,7 +112,12 @@ struct DArgs {
     int N, H, W, Cin, Cout, Cout_pad, P, log2g, splits, taps;
 };
 
-template <bool K64, bool CPG1>
+// W4: the weight codes are 4 bits wide, two per byte (see the weight kernels for the packing of a
+// 16-byte piece into 8).  A weight loader fetches the 8 packed bytes of its 16-byte LDS piece and
+// unpacks them on the way into LDS as 16 * code (a nibble moved to the top of its byte), so the
+// MFMA loop is the 8-bit one; the factor 16 leaves with the weight scales, which are staged as
+// sw / 16 (exact), and 16 * |sum| stays below 2^24 for every group size.
+template <bool K64, bool CPG1, bool W4>
 __global__ __launch_bounds__(256, 2) void k_direct_conv(const DArgs a) {
     constexpr int KSTEP = K64 ? 64 : 32, KB = KSTEP / 4;
     constexpr int BLK = 16 * KSTEP;   // bytes of one K-step of a 16-row block
@@ -128,7 +134,8 @@ __global__ __launch_bounds__(256, 2) void k_direct_conv(const DArgs a) {
     const int cpg_mask = ((1 << a.log2g) / KSTEP) - 1;
 
     const __amdgpu_buffer_rsrc_t rW = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<int8_t *>(a.Wq), 0, (int)((unsigned)a.taps * (unsigned)Cout_pad * (unsigned)Cin), kBufFlags);
+        const_cast<int8_t *>(a.Wq), 0,
+        (int)(((unsigned)a.taps * (unsigned)Cout_pad * (unsigned)Cin) >> (W4 ? 1 : 0)), kBufFlags);
     const __amdgpu_buffer_rsrc_t rX = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<int8_t *>(a.xq), 0, (int)((unsigned)P * (unsigned)Cin), kBufFlags);
     const __amdgpu_buffer_rsrc_t rSW = __builtin_amdgcn_make_buffer_rsrc(
@@ -145,7 +152,7 @@ __global__ __launch_bounds__(256, 2) void k_direct_conv(const DArgs a) {
     unsigned vW = kInvalid;
     {
         const int c = K64 ? tid : (tid & 127), blk = c / (BLK / 16), off = (c % (BLK / 16)) * 16;
-        if ((ob0 + blk) * 16 < Cout_pad) vW = (unsigned)((ob0 + blk) * 16 * Cin + off);
+        if ((ob0 + blk) * 16 < Cout_pad) vW = (unsigned)((ob0 + blk) * 16 * Cin + off) >> (W4 ? 1 : 0);
     }
     // pixel row and 16-byte piece of the gather, and where the piece goes in MFMA operand order
     const int xr = K64 ? (tid >> 2) : ((tid & 127) >> 1);   // row 0..63 inside the pixel tile
@@ -191,9 +198,13 @@ __global__ __launch_bounds__(256, 2) void k_direct_conv(const DArgs a) {
     float psc[PD];
     // the loader walks (tap t, K-step s) in order; its cursor is kept incrementally (uniform
     // scalars) and stops at the last step, which the tail of the ring fetches again
-    // this workgroup's taps: [t_beg, t_end) (all 9, a row of the window, or a single tap)
-    const int tps = a.taps / a.splits, t_beg = (int)blockIdx.z * tps, t_end = t_beg + tps;
-    int t_f = t_beg, s_f = 0, dp_f = a.taps == 1 ? 0 : (t_beg / 3 - 1) * W + (t_beg % 3 - 1);
+    // this workgroup's share of the reduction: taps [t_beg, t_end) (all 9, a row of the window, or
+    // a single tap) times K-steps [s_beg, s_end) (all of them; a linear layer with few rows splits
+    // its one tap along K instead, in whole groups)
+    const bool ksplit = a.taps == 1;
+    const int tps = ksplit ? 1 : a.taps / a.splits, t_beg = ksplit ? 0 : (int)blockIdx.z * tps, t_end = t_beg + tps;
+    const int sps = ksplit ? cps / a.splits : cps, s_beg = ksplit ? (int)blockIdx.z * sps : 0, s_end = s_beg + sps;
+    int t_f = t_beg, s_f = s_beg, dp_f = a.taps == 1 ? 0 : (t_beg / 3 - 1) * W + (t_beg % 3 - 1);
     auto fetch = [&](v4i (&dst)[LPT], float &dsc) {
         const int t = t_f, s = s_f, dp = dp_f;
         const unsigned gam = (unsigned)(s * KSTEP) >> a.log2g;
@@ -201,11 +212,18 @@ __global__ __launch_bounds__(256, 2) void k_direct_conv(const DArgs a) {
         const unsigned vX = ((nb >> t) & 1u)
                                 ? (unsigned)(prow + dp) * (unsigned)Cin + (unsigned)(s * KSTEP + xpc * 16)
                                 : kInvalid;
-        const unsigned soW = (unsigned)t * Cout_pad * Cin + (unsigned)s * BLK;
+        const unsigned soW = ((unsigned)t * Cout_pad * Cin + (unsigned)s * BLK) >> (W4 ? 1 : 0);
         if constexpr (K64) {
-            dst[0] = __builtin_amdgcn_raw_buffer_load_b128(rW, vW, soW, 0);
+            if constexpr (W4) {
+                const v2i pk = __builtin_amdgcn_raw_buffer_load_b64(rW, vW, soW, 0);
+                dst[0] = v4i{pk.x, pk.y, 0, 0};
+            } else {
+                dst[0] = __builtin_amdgcn_raw_buffer_load_b128(rW, vW, soW, 0);
+            }
             dst[1] = __builtin_amdgcn_raw_buffer_load_b128(rX, vX, 0, 0);
         } else {
+            // (W4: a weight loader's 16 bytes are its 8 packed bytes and its neighbour's, which it
+            // ignores: one load instruction for both kinds of loader keeps the waves in step)
             dst[0] = __builtin_amdgcn_raw_buffer_load_b128(w_loader ? rW : rX, w_loader ? vW : vX,
                                                            w_loader ? soW : 0u, 0);
         }
@@ -214,9 +232,9 @@ __global__ __launch_bounds__(256, 2) void k_direct_conv(const DArgs a) {
                                                        : kInvalid);
         const unsigned so = sc_w ? ((unsigned)t * groups + gam) * (unsigned)Cout_pad * 4u : 0u;
         dsc = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(sc_w ? rSW : rSX, vs, so, 0));
-        if (!(t_f == t_end - 1 && s_f == cps - 1)) {   // advance unless this was the last step
-            if (++s_f == cps) {
-                s_f = 0;
+        if (!(t_f == t_end - 1 && s_f == s_end - 1)) {   // advance unless this was the last step
+            if (++s_f == s_end) {
+                s_f = s_beg;
                 ++t_f;
                 dp_f = (t_f == 3 || t_f == 6) ? dp_f + W - 2 : dp_f + 1;   // next row of the window, or next column
             }
@@ -224,20 +242,26 @@ __global__ __launch_bounds__(256, 2) void k_direct_conv(const DArgs a) {
     };
     // LDS position of a gathered pixel piece in MFMA operand order [block][q][row16][KB bytes]
     const int xblk = 4 + (xr >> 4), xr16 = xr & 15;
+    auto unpack = [](const v4i &pk) {   // 8 packed bytes -> 16 bytes of 16 * code
+        if constexpr (!W4) return pk;
+        const unsigned p0 = (unsigned)pk.x, p1 = (unsigned)pk.y;
+        return v4i{(int)((p0 << 4) & 0xf0f0f0f0u), (int)(p0 & 0xf0f0f0f0u),
+                   (int)((p1 << 4) & 0xf0f0f0f0u), (int)(p1 & 0xf0f0f0f0u)};
+    };
     auto commit = [&](int buf, const v4i (&src)[LPT], float ssc) {
         if constexpr (K64) {
-            *reinterpret_cast<v4i *>(&opnd[buf][tid * 16]) = src[0];
+            *reinterpret_cast<v4i *>(&opnd[buf][tid * 16]) = unpack(src[0]);
             *reinterpret_cast<v4i *>(&opnd[buf][xblk * BLK + xpc * 256 + xr16 * 16]) = src[1];
         } else {
             if (w_loader) {
-                *reinterpret_cast<v4i *>(&opnd[buf][tid * 16]) = src[0];
+                *reinterpret_cast<v4i *>(&opnd[buf][tid * 16]) = unpack(src[0]);
             } else {   // 16 bytes = two K-quarters of 8 bytes
                 char *d = &opnd[buf][xblk * BLK + (2 * xpc) * 128 + xr16 * 8];
                 *reinterpret_cast<v2i *>(d) = v2i{src[0].x, src[0].y};
                 *reinterpret_cast<v2i *>(d + 128) = v2i{src[0].z, src[0].w};
             }
         }
-        if (w < 2) sc[buf][w * 64 + lane] = ssc;
+        if (w < 2) sc[buf][w * 64 + lane] = (W4 && w == 0) ? ssc * 0.0625f : ssc;
     };
 
     v4i acc[2][2];
@@ -250,7 +274,7 @@ __global__ __launch_bounds__(256, 2) void k_direct_conv(const DArgs a) {
             Mc[no][nt] = make_float4(0.f, 0.f, 0.f, 0.f);
         }
 
-    const int NI = tps * cps;
+    const int NI = tps * sps;
 #pragma unroll
     for (int u = 0; u < PD; ++u) fetch(pre[u], psc[u]);
     commit(0, pre[0], psc[0]);
@@ -289,7 +313,7 @@ __global__ __launch_bounds__(256, 2) void k_direct_conv(const DArgs a) {
                     acc[no][nt] = __builtin_amdgcn_mfma_i32_16x16x32_i8(x, y, c0, 0, 0, 0);
                 }
             }
-        if (CPG1 || ((it + 1) & cpg_mask) == 0) {   // last K-step of a group (cps is a multiple of the group's K-steps)
+        if (CPG1 || ((it + 1) & cpg_mask) == 0) {   // last K-step of a group (a share is a whole number of groups)
 #pragma unroll
             for (int no = 0; no < 2; ++no) {
                 const v4f sw = *reinterpret_cast<const v4f *>(&sc[buf][(2 * wn + no) * 16 + 4 * q]);
@@ -362,9 +386,10 @@ uint64_t align256(uint64_t v) { return (v + 255) / 256 * 256; }
 extern "C" {
 
 static wq_status_t make_plan(wq_direct_plan_t **out, int N, int H, int W, int Cin, int Cout,
-                             int group_size, int taps) {
+                             int group_size, int taps, int weight_bits) {
     if (!out) return WQ_ERR_INVALID_ARG;
     *out = nullptr;
+    if (weight_bits != 8 && weight_bits != 4) return WQ_ERR_UNSUPPORTED;
     if (N <= 0 || H <= 0 || W <= 0 || Cin <= 0 || Cout <= 0 || group_size <= 0) return WQ_ERR_INVALID_ARG;
     if (group_size != 32 && group_size != 64 && group_size != 128 && group_size != 256 && group_size != 512)
         return WQ_ERR_UNSUPPORTED;
@@ -380,12 +405,13 @@ static wq_status_t make_plan(wq_direct_plan_t **out, int N, int H, int W, int Ci
     p->groups = Cin / group_size; p->P = (int)P; p->Cout_pad = (int)Cp;
     p->kstep = group_size == 32 ? 32 : 64;
     p->taps = taps;
+    p->wbits = weight_bits;
     // the weight stage: the offline Winograd weight kernel as F(1,3) with G = I leaves the nine
     // filter taps untransformed and quantizes them per (tap, out-channel, group)
     wq_plan &w = p->w;
     w.N = N; w.H = H; w.W = W; w.Cin = Cin; w.Cout = Cout; w.m = 1; w.n = 3; w.g = group_size;
     w.groups = p->groups; w.TH = H; w.TW = W; w.T = (int)P; w.T_pad = (int)((P + 31) / 32 * 32);
-    w.Cout_pad = p->Cout_pad; w.kstep = p->kstep;
+    w.Cout_pad = p->Cout_pad; w.kstep = p->kstep; w.wbits = weight_bits;
     std::memset(&w.xf, 0, sizeof(w.xf));
     w.xf.G[0] = w.xf.G[4] = w.xf.G[8] = 1.0f;
     w.sparse_bt = w.sparse_g = w.sparse_at = false;
@@ -395,8 +421,10 @@ static wq_status_t make_plan(wq_direct_plan_t **out, int N, int H, int W, int Ci
     L.N = N; L.H = H; L.W = W; L.Cin = Cin; L.Cout = Cout; L.group_size = group_size;
     L.groups = p->groups; L.P = p->P; L.Cout_pad = p->Cout_pad; L.kstep = p->kstep;
     L.taps = taps;
+    L.weight_bits = weight_bits;
+    L.reserved = 0;
     L.blob_Wq_off = 0;
-    L.blob_sW_off = align256((uint64_t)taps * p->Cout_pad * Cin);
+    L.blob_sW_off = align256(((uint64_t)taps * p->Cout_pad * Cin * weight_bits) / 8);
     L.blob_bias_off = L.blob_sW_off + align256((uint64_t)taps * p->groups * p->Cout_pad * 4);
     L.blob_bytes = L.blob_bias_off + align256((uint64_t)p->Cout_pad * 4);
     L.ws_xq_off = 0;
@@ -409,7 +437,18 @@ static wq_status_t make_plan(wq_direct_plan_t **out, int N, int H, int W, int Ci
         const int v = std::atoi(e);
         if (v == 1 || v == 3 || v == 9) p->splits = v;
     }
-    if (taps == 1) p->splits = 1;
+    if (taps == 1) {
+        // a linear layer with few rows: split K, in whole groups, until the chip has enough
+        // workgroups (the partial sums are added by the same small kernel)
+        p->splits = 1;
+        while (base * p->splits < 512 && p->splits < 16 && p->groups % (p->splits * 2) == 0 &&
+               Cin / (p->splits * 2) >= 256)
+            p->splits *= 2;
+        if (const char *e = std::getenv("WQ_LINEAR_SPLITS")) {
+            const int v = std::atoi(e);
+            if (v >= 1 && v <= 16 && (v & (v - 1)) == 0 && p->groups % v == 0) p->splits = v;
+        }
+    }
     L.splits = p->splits;
     L.ws_part_off = L.ws_sx_off + align256((uint64_t)P * p->groups * 4);
     L.ws_bytes = L.ws_part_off + (p->splits > 1 ? align256((uint64_t)p->splits * P * Cout * 4) : 0);
@@ -420,11 +459,21 @@ static wq_status_t make_plan(wq_direct_plan_t **out, int N, int H, int W, int Ci
 
 wq_status_t wq_direct_plan_create(wq_direct_plan_t **out, int N, int H, int W, int Cin, int Cout,
                                   int group_size) {
-    return make_plan(out, N, H, W, Cin, Cout, group_size, 9);
+    return make_plan(out, N, H, W, Cin, Cout, group_size, 9, 8);
+}
+
+wq_status_t wq_direct_plan_create_bits(wq_direct_plan_t **out, int N, int H, int W, int Cin, int Cout,
+                                       int group_size, int weight_bits) {
+    return make_plan(out, N, H, W, Cin, Cout, group_size, 9, weight_bits);
 }
 
 wq_status_t wq_linear_plan_create(wq_direct_plan_t **out, int R, int Cin, int Cout, int group_size) {
-    return make_plan(out, R, 1, 1, Cin, Cout, group_size, 1);
+    return make_plan(out, R, 1, 1, Cin, Cout, group_size, 1, 8);
+}
+
+wq_status_t wq_linear_plan_create_bits(wq_direct_plan_t **out, int R, int Cin, int Cout, int group_size,
+                                       int weight_bits) {
+    return make_plan(out, R, 1, 1, Cin, Cout, group_size, 1, weight_bits);
 }
 
 wq_status_t wq_direct_plan_destroy(wq_direct_plan_t *plan) {
@@ -494,9 +543,15 @@ wq_status_t wq_direct_conv(const wq_direct_plan_t *plan, void *stream, void *wor
     const dim3 grid((unsigned)((plan->Cout_pad + 63) / 64), (unsigned)((plan->P + 63) / 64),
                     (unsigned)plan->splits), block(256);
     hipStream_t s = (hipStream_t)stream;
-    if (plan->kstep == 32) hipLaunchKernelGGL((k_direct_conv<false, true>), grid, block, 0, s, a);
-    else if (plan->g == 64) hipLaunchKernelGGL((k_direct_conv<true, true>), grid, block, 0, s, a);
-    else hipLaunchKernelGGL((k_direct_conv<true, false>), grid, block, 0, s, a);
+    if (plan->wbits == 4) {
+        if (plan->kstep == 32) hipLaunchKernelGGL((k_direct_conv<false, true, true>), grid, block, 0, s, a);
+        else if (plan->g == 64) hipLaunchKernelGGL((k_direct_conv<true, true, true>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((k_direct_conv<true, false, true>), grid, block, 0, s, a);
+    } else {
+        if (plan->kstep == 32) hipLaunchKernelGGL((k_direct_conv<false, true, false>), grid, block, 0, s, a);
+        else if (plan->g == 64) hipLaunchKernelGGL((k_direct_conv<true, true, false>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((k_direct_conv<true, false, false>), grid, block, 0, s, a);
+    }
     if (hipGetLastError() != hipSuccess) return WQ_ERR_DEVICE;
     if (plan->splits > 1) {
         const int total = plan->P * plan->Cout;

@@ -186,6 +186,7 @@ wq_status_t wq_plan_create(wq_plan_t **out, int N, int H, int W, int Cin, int Co
     p->T_pad = (int)((T + 31) / 32 * 32);
     p->Cout_pad = (Cout + 31) / 32 * 32;
     p->kstep = group_size == 32 ? 32 : 64;
+    p->wbits = 8;
     // Path for stages 2+3 (measured on MI355X): with few tiles the Winograd-domain result is
     // small next to the operands, and a tiled GEMM per tap plus a separate output transform
     // beats the fused kernel; so it does for very wide layers and for groups of 128 and more,

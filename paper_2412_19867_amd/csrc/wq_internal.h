@@ -24,6 +24,7 @@ struct wq_plan {
     int N, H, W, Cin, Cout, m, n, g, groups;
     int TH, TW, T, T_pad, Cout_pad;
     int kstep;   // K bytes per MFMA step and per block of the operand layout: 32 (g = 32) or 64
+    int wbits;   // width of the weight codes: 8, or 4 (two codes per byte; standard convolution and linear layers only)
     wq_xf xf;
     // true when the zero entries of the standard matrices are also zero here
     // (always the case for diagonal rescalings of the standard matrices), so

@@ -121,7 +121,10 @@ __device__ __forceinline__ CodePlace code_place(int tid, int kstep_log2, unsigne
 //   log2k        log2(units per group); the workgroup holds 16>>log2k rows-of-groups
 //   code_rsrc    buffer over the int8 tensor
 //   scale index  scale_base + t*scale_plane + item (item = row-of-group index inside the workgroup)
-template <int NT>
+//   W4           4-bit codes in [-7, 7] (scale a/7), two per byte: the 16-byte piece of int8 codes
+//                d0..d3 leaves as 8 bytes p0 p1 at half the byte offset, byte j of p0 holding byte j
+//                of d0 in its low and byte j of d1 in its high nibble (p1 likewise from d2, d3)
+template <int NT, bool W4 = false>
 __device__ __forceinline__ void quantize_and_store(const float2 (&vals)[NT], uint4 (*amax_s)[16],
                                                    float (*r_s)[16], char *codes_s, int log2k, int t0,
                                                    __amdgpu_buffer_rsrc_t code_rsrc, CodePlace place,
@@ -139,10 +142,11 @@ __device__ __forceinline__ void quantize_and_store(const float2 (&vals)[NT], uin
             a = max(max(a, max(v.x, v.y)), max(v.z, v.w));
         }
         const float af = __uint_as_float(a);
+        constexpr float QMAX = W4 ? 7.0f : 127.0f;
         float s = 0.0f, r = 0.0f;
-        if (af >= 127.0f * FLT_MIN) {
-            s = af / 127.0f;   // correctly rounded (hipcc default for fp32 division)
-            r = 127.0f / af;
+        if (af >= QMAX * FLT_MIN) {
+            s = af / QMAX;   // correctly rounded (hipcc default for fp32 division)
+            r = QMAX / af;
         }
         r_s[tl][item] = r;
         if (item < items_ok) scales[scale_base + (long)(t0 + tl) * scale_plane + item] = s;
@@ -162,8 +166,15 @@ __device__ __forceinline__ void quantize_and_store(const float2 (&vals)[NT], uin
 #pragma unroll
     for (int tl = tid >> 5; tl < NT; tl += 8) {
         const v4i v = *reinterpret_cast<const v4i *>(codes_s + tl * kTapStride + place.piece_pos);
-        __builtin_amdgcn_raw_buffer_store_b128(v, code_rsrc, place.piece_off,
-                                               (unsigned)(t0 + tl) * plane_bytes, kWriteThrough);
+        if constexpr (W4) {
+            const v2i pk = {(int)(((unsigned)v.x & 0x0f0f0f0fu) | (((unsigned)v.y << 4) & 0xf0f0f0f0u)),
+                            (int)(((unsigned)v.z & 0x0f0f0f0fu) | (((unsigned)v.w << 4) & 0xf0f0f0f0u))};
+            __builtin_amdgcn_raw_buffer_store_b64(pk, code_rsrc, place.piece_off >> 1,
+                                                  (unsigned)(t0 + tl) * (plane_bytes >> 1), kWriteThrough);
+        } else {
+            __builtin_amdgcn_raw_buffer_store_b128(v, code_rsrc, place.piece_off,
+                                                   (unsigned)(t0 + tl) * plane_bytes, kWriteThrough);
+        }
     }
 }
 
@@ -306,7 +317,7 @@ __global__ __launch_bounds__(256) void k_input_transform(wq_xf xf, const float *
 }
 
 // ----------------------------------------------------------- offline stage
-template <int M, bool SPARSE>
+template <int M, bool SPARSE, bool W4 = false>
 __global__ __launch_bounds__(256) void k_weight_transform(wq_xf xf, const float *__restrict__ w,
                                                           int8_t *__restrict__ Wq,
                                                           float *__restrict__ sW, int Cin, int Cout,
@@ -375,7 +386,7 @@ __global__ __launch_bounds__(256) void k_weight_transform(wq_xf xf, const float 
         }
     }
     const __amdgpu_buffer_rsrc_t rq = __builtin_amdgcn_make_buffer_rsrc(
-        Wq, 0, (int)((unsigned)n2 * (unsigned)Cout_pad * (unsigned)Cin), kBufFlags);
+        Wq, 0, (int)(((unsigned)n2 * (unsigned)Cout_pad * (unsigned)Cin) >> (W4 ? 1 : 0)), kBufFlags);
     const CodePlace place =
         code_place(tid, kstep_log2, (unsigned)rb * 16u * (unsigned)Cin, [&](int r, int &c, int &r16) {
             c = gam * k + (r & (k - 1));
@@ -383,9 +394,9 @@ __global__ __launch_bounds__(256) void k_weight_transform(wq_xf xf, const float 
         });
     // sW [t][group][Cout_pad]: this workgroup owns 16/k consecutive output channels
     const long scale_base = (long)gam * Cout_pad + rb * 16 + sub * (16 >> log2k);
-    quantize_and_store<n2>(X, amax_s, r_s, codes_s, log2k, 0, rq, place,
-                           (unsigned)Cout_pad * (unsigned)Cin, sW, scale_base,
-                           (long)groups * Cout_pad, 16);
+    quantize_and_store<n2, W4>(X, amax_s, r_s, codes_s, log2k, 0, rq, place,
+                               (unsigned)Cout_pad * (unsigned)Cin, sW, scale_base,
+                               (long)groups * Cout_pad, 16);
 }
 
 __global__ void k_copy_bias(const float *__restrict__ bias, float *__restrict__ out, int Cout,
@@ -396,6 +407,7 @@ __global__ void k_copy_bias(const float *__restrict__ bias, float *__restrict__ 
 
 // Group-wise quantization of a plain weight matrix w [Cout][Cin] (a linear layer, or a 1x1
 // convolution): the offline weight stage without a transform, one tap.
+template <bool W4>
 __global__ __launch_bounds__(256) void k_quantize_weight_rows(const float *__restrict__ w,
                                                               int8_t *__restrict__ Wq,
                                                               float *__restrict__ sW, int Cin, int Cout,
@@ -416,16 +428,16 @@ __global__ __launch_bounds__(256) void k_quantize_weight_rows(const float *__res
                     : make_float2(0.0f, 0.0f);
     reinterpret_cast<uint32_t *>(&amax_s[0][row])[l16 >> 2] = quad_max(abs_max_bits(X[0].x, X[0].y));
     const __amdgpu_buffer_rsrc_t rq = __builtin_amdgcn_make_buffer_rsrc(
-        Wq, 0, (int)((unsigned)Cout_pad * (unsigned)Cin), kBufFlags);
+        Wq, 0, (int)(((unsigned)Cout_pad * (unsigned)Cin) >> (W4 ? 1 : 0)), kBufFlags);
     const CodePlace place =
         code_place(tid, kstep_log2, (unsigned)rb * 16u * (unsigned)Cin, [&](int r, int &c, int &r16) {
             c = gam * k + (r & (k - 1));
             r16 = sub * (16 >> log2k) + (r >> log2k);
         });
     const long scale_base = (long)gam * Cout_pad + rb * 16 + sub * (16 >> log2k);
-    quantize_and_store<1>(X, amax_s, r_s, codes_s, log2k, 0, rq, place,
-                          (unsigned)Cout_pad * (unsigned)Cin, sW, scale_base,
-                          (long)groups * Cout_pad, 16);
+    quantize_and_store<1, W4>(X, amax_s, r_s, codes_s, log2k, 0, rq, place,
+                              (unsigned)Cout_pad * (unsigned)Cin, sW, scale_base,
+                              (long)groups * Cout_pad, 16);
 }
 
 int ilog2(int v) {
@@ -463,6 +475,13 @@ template <int M>
 hipError_t launch_weight_m(const wq_plan *p, hipStream_t s, const float *w, int8_t *Wq, float *sW) {
     const dim3 grid((unsigned)((p->Cout_pad / 16) * (p->Cin / 32))), block(256);
     const int log2k = ilog2(p->g / 32), kstep_log2 = p->kstep == 32 ? 5 : 6;
+    if constexpr (M == 1) {   // the untransformed taps of a standard convolution: also with 4-bit codes
+        if (p->wbits == 4) {
+            hipLaunchKernelGGL((k_weight_transform<M, false, true>), grid, block, 0, s, p->xf, w, Wq, sW,
+                               p->Cin, p->Cout, p->Cout_pad, log2k, kstep_log2);
+            return hipGetLastError();
+        }
+    }
     if (p->sparse_g)
         hipLaunchKernelGGL((k_weight_transform<M, true>), grid, block, 0, s, p->xf, w, Wq, sW,
                            p->Cin, p->Cout, p->Cout_pad, log2k, kstep_log2);
@@ -485,8 +504,12 @@ hipError_t wq_launch_input(const wq_plan *p, hipStream_t s, const float *x, int8
 hipError_t wq_launch_weight_rows(const wq_plan *p, hipStream_t s, const float *w, const float *bias,
                                  int8_t *Wq, float *sW, float *bias_out) {
     const dim3 grid((unsigned)((p->Cout_pad / 16) * (p->Cin / 32))), block(256);
-    hipLaunchKernelGGL(k_quantize_weight_rows, grid, block, 0, s, w, Wq, sW, p->Cin, p->Cout,
-                       p->Cout_pad, ilog2(p->g / 32), p->kstep == 32 ? 5 : 6);
+    if (p->wbits == 4)
+        hipLaunchKernelGGL((k_quantize_weight_rows<true>), grid, block, 0, s, w, Wq, sW, p->Cin, p->Cout,
+                           p->Cout_pad, ilog2(p->g / 32), p->kstep == 32 ? 5 : 6);
+    else
+        hipLaunchKernelGGL((k_quantize_weight_rows<false>), grid, block, 0, s, w, Wq, sW, p->Cin, p->Cout,
+                           p->Cout_pad, ilog2(p->g / 32), p->kstep == 32 ? 5 : 6);
     if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
     hipLaunchKernelGGL(k_copy_bias, dim3((p->Cout_pad + 255) / 256), dim3(256), 0, s, bias, bias_out,
                        p->Cout, p->Cout_pad);

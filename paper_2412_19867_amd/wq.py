@@ -22,7 +22,8 @@ STATUS_NAMES = {0: "WQ_OK", 1: "WQ_ERR_INVALID_ARG", 2: "WQ_ERR_UNSUPPORTED",
 EXPORTS = ["wq_standard_transforms", "wq_plan_create", "wq_plan_destroy", "wq_plan_layout",
            "wq_weight_prepare", "wq_input_transform", "wq_contract_output", "wq_contract",
            "wq_output_transform", "wq_conv_forward",
-           "wq_direct_plan_create", "wq_linear_plan_create", "wq_direct_plan_destroy", "wq_direct_plan_layout",
+           "wq_direct_plan_create", "wq_linear_plan_create", "wq_direct_plan_create_bits",
+           "wq_linear_plan_create_bits", "wq_direct_plan_destroy", "wq_direct_plan_layout",
            "wq_direct_weight_prepare", "wq_direct_quantize", "wq_direct_conv", "wq_direct_forward",
            "wq_conv_forward_debug", "wq_status_string"]
 
@@ -39,7 +40,7 @@ class Layout(ctypes.Structure):
 class DirectLayout(ctypes.Structure):
     _fields_ = ([(k, ctypes.c_int32) for k in
                  ("N", "H", "W", "Cin", "Cout", "group_size", "groups", "P", "Cout_pad", "kstep",
-                  "splits", "taps")] +
+                  "splits", "taps", "weight_bits", "reserved")] +
                 [(k, ctypes.c_uint64) for k in
                  ("blob_bytes", "blob_Wq_off", "blob_sW_off", "blob_bias_off",
                   "ws_bytes", "ws_xq_off", "ws_sx_off", "ws_part_off")])
@@ -76,6 +77,8 @@ def lib() -> ctypes.CDLL:
         L.wq_conv_forward_debug.argtypes = [vp, vp, vp, vp, sz, vp, sz, vp, vp, sz]
         L.wq_direct_plan_create.argtypes = [ctypes.POINTER(vp), ip, ip, ip, ip, ip, ip]
         L.wq_linear_plan_create.argtypes = [ctypes.POINTER(vp), ip, ip, ip, ip]
+        L.wq_direct_plan_create_bits.argtypes = [ctypes.POINTER(vp), ip, ip, ip, ip, ip, ip, ip]
+        L.wq_linear_plan_create_bits.argtypes = [ctypes.POINTER(vp), ip, ip, ip, ip, ip]
         L.wq_direct_plan_destroy.argtypes = [vp]
         L.wq_direct_plan_layout.argtypes = [vp, ctypes.POINTER(DirectLayout)]
         L.wq_direct_weight_prepare.argtypes = [vp, vp, vp, vp, vp, sz]
@@ -297,14 +300,14 @@ class DirectPlan:
     """The group-wise quantized standard 3x3 convolution (the paper's runtime
     comparison point) for one layer shape.  Owns only the host-side plan object."""
 
-    def __init__(self, N, H, W, Cin, Cout, group_size, linear: bool = False):
+    def __init__(self, N, H, W, Cin, Cout, group_size, linear: bool = False, weight_bits: int = 8):
         self._h = ctypes.c_void_p()
         if linear:   # N rows, H = W = 1: a group-wise quantized linear layer
-            _check(lib().wq_linear_plan_create(ctypes.byref(self._h), N * H * W, Cin, Cout, group_size),
-                   "wq_linear_plan_create")
+            _check(lib().wq_linear_plan_create_bits(ctypes.byref(self._h), N * H * W, Cin, Cout, group_size,
+                                                    weight_bits), "wq_linear_plan_create_bits")
         else:
-            _check(lib().wq_direct_plan_create(ctypes.byref(self._h), N, H, W, Cin, Cout, group_size),
-                   "wq_direct_plan_create")
+            _check(lib().wq_direct_plan_create_bits(ctypes.byref(self._h), N, H, W, Cin, Cout, group_size,
+                                                    weight_bits), "wq_direct_plan_create_bits")
         self.layout = DirectLayout()
         _check(lib().wq_direct_plan_layout(self._h, ctypes.byref(self.layout)), "wq_direct_plan_layout")
 
@@ -333,7 +336,13 @@ class DirectPlan:
         import torch
         L = self.layout
         R, ks, nt = L.Cout_pad, L.kstep, L.taps
-        raw = blob[L.blob_Wq_off:L.blob_Wq_off + nt * R * L.Cin].view(torch.int8)
+        if L.weight_bits == 4:   # two codes per byte: back to one int8 per code, same blocked order
+            pk = blob[L.blob_Wq_off:L.blob_Wq_off + nt * R * L.Cin // 2].view(-1, 2, 4)   # pieces p0 p1
+            lo = ((pk & 0x0f) ^ 0x08).to(torch.int16) - 8      # sign-extend the low nibbles: d0, d2
+            hi = ((pk >> 4) ^ 0x08).to(torch.int16) - 8        # and the high ones: d1, d3
+            raw = torch.stack((lo, hi), dim=2).to(torch.int8).reshape(-1)   # d0 d1 d2 d3 per piece
+        else:
+            raw = blob[L.blob_Wq_off:L.blob_Wq_off + nt * R * L.Cin].view(torch.int8)
         Wq = raw.view(nt, R // 16, L.Cin // ks, 4, 16, ks // 4).permute(0, 1, 4, 2, 3, 5) \
             .reshape(nt, R, L.Cin)
         sW = blob[L.blob_sW_off:L.blob_sW_off + nt * L.groups * R * 4].view(torch.float32) \

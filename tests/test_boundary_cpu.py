@@ -185,3 +185,18 @@ def test_direct_plan_refuses_more_pixels_than_the_launch_grid_holds(wq):
     assert lib.wq_direct_plan_create(ctypes.byref(h), 1, 2048, 2048, 32, 32, 32) == 2   # WQ_ERR_UNSUPPORTED
     assert lib.wq_direct_plan_create(ctypes.byref(h), 1, 2047, 2048, 32, 32, 32) == 0
     lib.wq_direct_plan_destroy(h)
+
+
+def test_weight_bits_of_direct_and_linear_plans(wq):
+    lib = wq.lib()
+    h = ctypes.c_void_p()
+    assert lib.wq_linear_plan_create_bits(ctypes.byref(h), 8, 64, 8, 32, 5) == 2    # WQ_ERR_UNSUPPORTED
+    assert lib.wq_direct_plan_create_bits(ctypes.byref(h), 1, 4, 4, 64, 8, 32, 16) == 2
+    p8 = wq.DirectPlan(10, 1, 1, 128, 40, 32, linear=True)
+    p4 = wq.DirectPlan(10, 1, 1, 128, 40, 32, linear=True, weight_bits=4)
+    assert p8.layout.weight_bits == 8 and p4.layout.weight_bits == 4
+    assert p4.layout.blob_sW_off == (64 * 128 // 2 + 255) // 256 * 256       # Cout_pad = 64, two codes per byte
+    assert p8.layout.blob_sW_off == 64 * 128
+    assert p4.layout.ws_bytes == p8.layout.ws_bytes
+    c4 = wq.DirectPlan(1, 5, 5, 64, 16, 32, weight_bits=4)
+    assert c4.layout.taps == 9 and c4.layout.blob_sW_off == (9 * 32 * 64 // 2 + 255) // 256 * 256

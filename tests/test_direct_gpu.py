@@ -1,4 +1,5 @@
-"""GPU parity of the group-wise quantized standard convolution against its oracle.
+"""GPU parity of the group-wise quantized standard convolution against its oracle, with 8-bit
+and with 4-bit weight codes (W8A8, W4A8).
 
 Bit-exact on the int8 codes and the fp32 scales of activations and weights; fp32
 output within 1e-5 of the layer's largest output magnitude.
@@ -15,10 +16,10 @@ pytestmark = pytest.mark.gpu
 Y_TOL = 1e-5
 
 
-def run_direct(wq, x, w, bias, g):
+def run_direct(wq, x, w, bias, g, bits=8):
     N, H, W, Cin = x.shape
     Cout = w.shape[0]
-    plan = wq.DirectPlan(N, H, W, Cin, Cout, g)
+    plan = wq.DirectPlan(N, H, W, Cin, Cout, g, weight_bits=bits)
     L = plan.layout
     blob, ws, y = plan.alloc_blob(), plan.alloc_workspace(), plan.alloc_output()
     y.fill_(float("nan"))
@@ -35,9 +36,9 @@ def run_direct(wq, x, w, bias, g):
                             and (b[Cout:] == 0).all()))
 
 
-def check_direct(wq, x, w, bias, g, name):
-    ref = oracle.direct_pipeline(x, w, bias, g)
-    got = run_direct(wq, x, w, bias, g)
+def check_direct(wq, x, w, bias, g, name, bits=8):
+    ref = oracle.direct_pipeline(x, w, bias, g, weight_bits=bits)
+    got = run_direct(wq, x, w, bias, g, bits)
     assert got["pad_ok"]
     for key in ("wq", "xq"):
         bad = np.count_nonzero(got[key] != ref[key])
@@ -66,11 +67,12 @@ SMALL = [
 ]
 
 
+@pytest.mark.parametrize("bits", [8, 4], ids=["w8", "w4"])
 @pytest.mark.parametrize("case", SMALL, ids=lambda c: "d%d_%dx%dx%d_%d-%d_g%d" % c)
-def test_direct_small_layers(wq, case):
+def test_direct_small_layers(wq, case, bits):
     seed, N, H, W, Cin, Cout, g = case
     d = workloads.small_layer(seed, N, H, W, Cin, Cout, 4, g)
-    check_direct(wq, d.x, d.w, d.bias, g, "small%d" % seed)
+    check_direct(wq, d.x, d.w, d.bias, g, "small%d" % seed, bits)
 
 
 def test_direct_no_bias_and_zero_groups(wq):
@@ -91,6 +93,7 @@ def test_direct_config_layers_full_size(wq, cfg, idx):
     lay = workloads.CONFIGS[cfg][idx]
     d = workloads.make_layer_data(lay)
     check_direct(wq, d.x, d.w, d.bias, lay.group_size, lay.name)
+    check_direct(wq, d.x, d.w, d.bias, lay.group_size, lay.name + " W4A8", bits=4)
 
 
 def _random_cases(count, seed):
@@ -107,7 +110,7 @@ def _random_cases(count, seed):
 def test_direct_random_small_shapes(wq, case):
     seed, N, H, W, Cin, Cout, g = case
     d = workloads.small_layer(seed, N, H, W, Cin, Cout, 4, g)
-    check_direct(wq, d.x, d.w, d.bias, g, "random%d" % seed)
+    check_direct(wq, d.x, d.w, d.bias, g, "random%d" % seed, bits=8 if seed % 2 else 4)
 
 
 def test_direct_largest_pixel_count(wq):

@@ -245,3 +245,26 @@ def test_pipeline_bound_catches_a_misindexed_scale():
               + np.einsum("atc,aoc->ato", eX, eW))
     Mexact = np.einsum("atc,aoc->ato", Xf.astype(np.float64), Wf.astype(np.float64))
     assert np.any(np.abs(M_bad - Mexact) > boundM * 1.5)
+
+
+@pytest.mark.parametrize("m", [2, 4, 6])
+def test_power_of_two_row_scales_change_nothing_but_the_stored_scales(m):
+    """With transforms in fp32 and only X and W quantized, a diagonal rescaling of B^T and G
+    multiplies every tap by one factor for all channels; the dynamic abs-max scale of each
+    group absorbs it and S_A = (S_B S_G)^-1 undoes it.  For powers of two this holds exactly:
+    same int8 codes, scales multiplied by the tap's factor, same int32 sums, same output."""
+    n = m + 2
+    rng = np.random.default_rng(40 + m)
+    kB, kG = rng.integers(-3, 4, n), rng.integers(-3, 4, n)
+    mats0 = tuple(M.astype(np.float32) for M in ct.standard_matrices(m))
+    mats1 = tuple(M.astype(np.float32) for M in ct.scaled_matrices(m, 2.0 ** kB, 2.0 ** kG))
+    d = workloads.small_layer(60 + m, 2, 9, 7, 64, 24, m, 32)
+    r0 = oracle.qwino_pipeline(d.x, d.w, d.bias, *mats0, m, 32, want_P=True)
+    r1 = oracle.qwino_pipeline(d.x, d.w, d.bias, *mats1, m, 32, want_P=True)
+    assert np.array_equal(r0["Xq"], r1["Xq"]) and np.array_equal(r0["Wq"], r1["Wq"])
+    assert np.array_equal(r0["P"], r1["P"])
+    fB = (2.0 ** (kB[:, None] + kB[None, :])).reshape(n * n).astype(np.float32)
+    fG = (2.0 ** (kG[:, None] + kG[None, :])).reshape(n * n).astype(np.float32)
+    assert np.array_equal(r1["sX"], r0["sX"] * fB[:, None, None])
+    assert np.array_equal(r1["sW"], r0["sW"] * fG[:, None, None])
+    assert np.array_equal(r0["y64"], r1["y64"])

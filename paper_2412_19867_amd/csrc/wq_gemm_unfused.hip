@@ -38,6 +38,10 @@ struct GArgs {
     const float *sW;
     float *Mbuf;
     int Cin, T_pad, Cout_pad, log2g, n2;
+    // workgroup tiles along channels and tiles, their product with the taps, and the share of
+    // each XCD (set by the launcher)
+    int nOBt, nTBt, total, per_xcd;
+    int m_plain_stores;   // cache policy of the product tensor's stores (see the kernel's end)
 };
 
 // TBW = 16-tile blocks per workgroup (4: a 64x64 output tile, waves 2x2; 2: 32 tiles x 128
@@ -59,7 +63,14 @@ __global__ __launch_bounds__(256, 2) void k_gemm_dequant(const GArgs a) {
 
     const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15, q = lane >> 4;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6), wm = w / WN, wn = w % WN;
-    const int t = blockIdx.z, ob0 = blockIdx.x * OBW, tb0 = blockIdx.y * TBW;   // in 16-row blocks
+    // Workgroup ids go round-robin over the 8 XCDs, whose L2s are private.  XCD x takes the
+    // logical tiles [x * per_xcd, (x + 1) * per_xcd) in order, channel tiles fastest, so that
+    // the workgroups resident on one XCD at a time are neighbours in (tap, tile, channel) and
+    // share their operand tiles in that L2 instead of every XCD fetching every tile.
+    const int logical = (int)(blockIdx.x & 7u) * a.per_xcd + (int)(blockIdx.x >> 3);
+    if (logical >= a.total) return;   // the whole workgroup leaves, before any barrier
+    const int t = logical / (a.nOBt * a.nTBt), rem = logical - t * (a.nOBt * a.nTBt);
+    const int ob0 = (rem % a.nOBt) * OBW, tb0 = (rem / a.nOBt) * TBW;   // in 16-row blocks
     const int Cin = a.Cin, T_pad = a.T_pad, Cout_pad = a.Cout_pad;
     const int groups = Cin >> a.log2g, cps = Cin / KSTEP;
     const int cpg_mask = ((1 << a.log2g) / KSTEP) - 1;
@@ -105,7 +116,10 @@ __global__ __launch_bounds__(256, 2) void k_gemm_dequant(const GArgs a) {
     // s & 1 while step s+1 moves from its ring slot into the other buffer.  Every wave
     // issues the same number of loads per K-step and no load sits under a branch, so the
     // wait before the move leaves the newer K-steps outstanding.
-    constexpr int PD = 2;   // measured: 2, 4, 6, 8 K-steps in flight; 2 is as fast as any and starts sooner
+#ifndef WQ_PD_BIG
+#define WQ_PD_BIG 2
+#endif
+    constexpr int PD = TBW == 8 ? WQ_PD_BIG : 2;   // measured: 2, 4, 6, 8 K-steps in flight; 2 is as fast as any and starts sooner
     v4i pre[PD][LPT];
     float psc[PD];
     auto fetch = [&](int s, v4i (&dst)[LPT], float &dsc) {   // global -> registers for K-step s
@@ -142,8 +156,16 @@ __global__ __launch_bounds__(256, 2) void k_gemm_dequant(const GArgs a) {
     int in_chunk = 0;
 
     const int last = cps - 1;
+    // The K loop starts at a group that depends on the workgroup and wraps round: workgroups
+    // that run side by side then read different K positions of their rows at any one time
+    // (their rows are a multiple of 256 bytes apart, so equal K positions land on the same
+    // few L2 channels; measured 4-7 % on layers with thousands of workgroups, nothing on
+    // small ones).  The integer sums of a group do not depend on the order; the fp32 sum
+    // over the groups is taken in the rotated order.
+    const int s0 = (logical % groups) * (cpg_mask + 1);
+    auto kpos = [&](int k) { const int v = k + s0; return v >= cps ? v - cps : v; };
 #pragma unroll
-    for (int u = 0; u < PD; ++u) fetch(min(u, last), pre[u], psc[u]);
+    for (int u = 0; u < PD; ++u) fetch(kpos(min(u, last)), pre[u], psc[u]);
     commit(0, pre[0], psc[0]);
     __syncthreads();
     for (int s0 = 0; s0 < cps; s0 += PD) {
@@ -152,7 +174,7 @@ __global__ __launch_bounds__(256, 2) void k_gemm_dequant(const GArgs a) {
         const int s = s0 + u;
         if (s >= cps) break;
         const int buf = u & 1;   // PD is even, so s & 1 == u & 1
-        fetch(min(s + PD, last), pre[u], psc[u]);   // slot u held step s, already in LDS
+        fetch(kpos(min(s + PD, last)), pre[u], psc[u]);   // slot u held step s, already in LDS
         // operands of this wave's BN x BM blocks
         v4i av[BN], bv[BM];
 #pragma unroll
@@ -234,11 +256,16 @@ __global__ __launch_bounds__(256, 2) void k_gemm_dequant(const GArgs a) {
                 Mv = make_float4((float)(Mt[no][nt][0] + (double)Mv.x), (float)(Mt[no][nt][1] + (double)Mv.y),
                                  (float)(Mt[no][nt][2] + (double)Mv.z), (float)(Mt[no][nt][3] + (double)Mv.w));
             const int tau = (tb0 + BM * wm + nt) * 16 + l16, o = (ob0 + BN * wn + no) * 16 + 4 * q;
-            if (tau < T_pad && o < Cout_pad)
-                __builtin_amdgcn_raw_buffer_store_b128(
-                    __builtin_bit_cast(v4i, v4f{Mv.x, Mv.y, Mv.z, Mv.w}), rM,
-                    (((unsigned)tau * n2 + (unsigned)t) * (unsigned)Cout_pad + (unsigned)o) * 4u, 0,
-                    kWriteThrough);
+            if (tau < T_pad && o < Cout_pad) {
+                const v4i bits = __builtin_bit_cast(v4i, v4f{Mv.x, Mv.y, Mv.z, Mv.w});
+                const unsigned off =
+                    (((unsigned)tau * n2 + (unsigned)t) * (unsigned)Cout_pad + (unsigned)o) * 4u;
+                // a product tensor far larger than the caches: plain stores; otherwise written
+                // through, which spares the flush at the kernel's end (each measured ~5 % better
+                // on its side)
+                if (a.m_plain_stores) __builtin_amdgcn_raw_buffer_store_b128(bits, rM, off, 0, 0);
+                else __builtin_amdgcn_raw_buffer_store_b128(bits, rM, off, 0, kWriteThrough);
+            }
         }
 }
 
@@ -301,23 +328,30 @@ __global__ __launch_bounds__(64 * M) void k_output_transform(const OArgs a) {
 }
 
 template <bool K64, bool CPG1>
-void launch_gemm(const GArgs &g, hipStream_t s, bool wide, bool narrow, bool big) {
-    const unsigned taps = (unsigned)g.n2;
+void launch_gemm(const GArgs &g0, hipStream_t s, bool wide, bool narrow, bool big) {
+    GArgs g = g0;
+    auto shape = [&](int ch_per_wg, int tiles_per_wg) {
+        g.nOBt = (g.Cout_pad + ch_per_wg - 1) / ch_per_wg;
+        g.nTBt = (g.T_pad + tiles_per_wg - 1) / tiles_per_wg;
+        g.total = g.nOBt * g.nTBt * g.n2;
+        g.per_xcd = (g.total + 7) / 8;
+        return dim3((unsigned)g.per_xcd * 8u);
+    };
     if constexpr (K64 && !CPG1) {
         if (big && !wide) {
-            const dim3 grid((g.Cout_pad + 127) / 128, (g.T_pad + 127) / 128, taps);
+            const dim3 grid = shape(128, 128);
             hipLaunchKernelGGL((k_gemm_dequant<true, false, false, 8>), grid, dim3(256), 0, s, g);
             return;
         }
     }
     if (narrow) {
-        const dim3 grid((g.Cout_pad + 127) / 128, g.T_pad / 32, taps);
+        const dim3 grid = shape(128, 32);
         if (wide)
             hipLaunchKernelGGL((k_gemm_dequant<K64, CPG1, true, 2>), grid, dim3(256), 0, s, g);
         else
             hipLaunchKernelGGL((k_gemm_dequant<K64, CPG1, false, 2>), grid, dim3(256), 0, s, g);
     } else {
-        const dim3 grid((g.Cout_pad + 63) / 64, (g.T_pad + 63) / 64, taps);
+        const dim3 grid = shape(64, 64);
         if (wide)
             hipLaunchKernelGGL((k_gemm_dequant<K64, CPG1, true, 4>), grid, dim3(256), 0, s, g);
         else
@@ -344,6 +378,7 @@ hipError_t wq_launch_contract_unfused(const wq_plan *p, hipStream_t s, const int
     g.Cin = p->Cin; g.T_pad = p->T_pad; g.Cout_pad = p->Cout_pad; g.n2 = p->n * p->n;
     g.log2g = 0;
     while ((1 << g.log2g) < p->g) ++g.log2g;
+    g.m_plain_stores = (long long)g.n2 * p->T_pad * p->Cout_pad * 4 > (128LL << 20);
     const bool k64 = p->kstep == 64, cpg1 = p->g == p->kstep, wide = p->groups > 8;
     // 32-tile workgroups when the 64-tile ones would leave half a tile row of blocks empty
     bool narrow = (p->T_pad % 64) == 32 && p->T_pad <= 160;

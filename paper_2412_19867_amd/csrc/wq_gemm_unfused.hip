@@ -116,10 +116,7 @@ __global__ __launch_bounds__(256, 2) void k_gemm_dequant(const GArgs a) {
     // s & 1 while step s+1 moves from its ring slot into the other buffer.  Every wave
     // issues the same number of loads per K-step and no load sits under a branch, so the
     // wait before the move leaves the newer K-steps outstanding.
-#ifndef WQ_PD_BIG
-#define WQ_PD_BIG 2
-#endif
-    constexpr int PD = TBW == 8 ? WQ_PD_BIG : 2;   // measured: 2, 4, 6, 8 K-steps in flight; 2 is as fast as any and starts sooner
+    constexpr int PD = 2;   // measured: 2, 4, 6, 8 K-steps in flight, on every tile variant; 2 is as fast as any and starts sooner
     v4i pre[PD][LPT];
     float psc[PD];
     auto fetch = [&](int s, v4i (&dst)[LPT], float &dsc) {   // global -> registers for K-step s

@@ -389,8 +389,8 @@ hipError_t launch_cfg(const Args &a, hipStream_t s) {
 inline int choose_cfg(const wq_plan *p) {
     if (!p->sparse_at || p->m == 2 || p->g > 64) return CFG_BASE;
     // tuning knob: WQ_K2_CONFIG=0..3 forces a configuration where it is applicable
-    if (const char *e = getenv("WQ_K2_CONFIG")) {
-        const int c = atoi(e);
+    if (p->force_k2_config > 0) {
+        const int c = p->force_k2_config - 1;
         if (c == CFG_KSPLIT && p->groups % 2 != 0) return CFG_BASE;
         if (c >= CFG_BASE && c <= CFG_BIG) return c;
     }

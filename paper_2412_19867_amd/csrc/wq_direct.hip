@@ -412,6 +412,7 @@ static wq_status_t make_plan(wq_direct_plan_t **out, int N, int H, int W, int Ci
     w.N = N; w.H = H; w.W = W; w.Cin = Cin; w.Cout = Cout; w.m = 1; w.n = 3; w.g = group_size;
     w.groups = p->groups; w.TH = H; w.TW = W; w.T = (int)P; w.T_pad = (int)((P + 31) / 32 * 32);
     w.Cout_pad = p->Cout_pad; w.kstep = p->kstep; w.wbits = weight_bits;
+    w.force_k1_rows = w.force_gemm_tile = w.force_k2_config = 0;
     std::memset(&w.xf, 0, sizeof(w.xf));
     w.xf.G[0] = w.xf.G[4] = w.xf.G[8] = 1.0f;
     w.sparse_bt = w.sparse_g = w.sparse_at = false;

@@ -379,16 +379,12 @@ hipError_t wq_launch_contract_unfused(const wq_plan *p, hipStream_t s, const int
     const bool k64 = p->kstep == 64, cpg1 = p->g == p->kstep, wide = p->groups > 8;
     // 32-tile workgroups when the 64-tile ones would leave half a tile row of blocks empty
     bool narrow = (p->T_pad % 64) == 32 && p->T_pad <= 160;
-    if (const char *e = std::getenv("WQ_GEMM_TILE")) {
-        if (!std::strcmp(e, "32")) narrow = true;
-        if (!std::strcmp(e, "64")) narrow = false;
-    }
+    if (p->force_gemm_tile == 32) narrow = true;
+    if (p->force_gemm_tile == 64) narrow = false;
     // 128x128 tiles: groups of 128 and more on layers with at least 1024 tiles and 256 channels
     bool big = p->g >= 128 && p->T_pad >= 1024 && p->Cout_pad >= 256;
-    if (const char *e = std::getenv("WQ_GEMM_TILE")) {
-        if (!std::strcmp(e, "128")) big = true;
-        if (!std::strcmp(e, "32") || !std::strcmp(e, "64")) big = false;
-    }
+    if (p->force_gemm_tile == 128) big = true;
+    if (p->force_gemm_tile == 32 || p->force_gemm_tile == 64) big = false;
     if (!k64) launch_gemm<false, true>(g, s, wide, narrow, big);
     else if (cpg1) launch_gemm<true, true>(g, s, wide, narrow, big);
     else launch_gemm<true, false>(g, s, wide, narrow, big);

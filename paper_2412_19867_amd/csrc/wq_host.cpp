@@ -198,6 +198,10 @@ wq_status_t wq_plan_create(wq_plan_t **out, int N, int H, int W, int Cin, int Co
         if (!std::strcmp(e, "fused")) p->two_kernel = false;
         if (!std::strcmp(e, "split")) p->two_kernel = true;
     }
+    p->force_k1_rows = p->force_gemm_tile = p->force_k2_config = 0;
+    if (const char *e = std::getenv("WQ_K1_ROWS")) p->force_k1_rows = std::atoi(e);
+    if (const char *e = std::getenv("WQ_GEMM_TILE")) p->force_gemm_tile = std::atoi(e);
+    if (const char *e = std::getenv("WQ_K2_CONFIG")) p->force_k2_config = std::atoi(e) + 1;
     p->prepared.store(0);
     std::memset(&p->xf, 0, sizeof(p->xf));
     if (all) {

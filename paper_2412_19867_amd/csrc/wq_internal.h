@@ -34,6 +34,10 @@ struct wq_plan {
     bool sparse_bt, sparse_g, sparse_at;
     // stages 2+3 as GEMM + separate output transform (few tiles, many channels) instead of fused
     bool two_kernel;
+    // tuning overrides read from the environment once, when the plan is made (0 = the library's
+    // own choice): WQ_K1_ROWS (tap rows per workgroup of the input kernel), WQ_GEMM_TILE (32, 64
+    // or 128 tiles per workgroup of the tiled GEMM), WQ_K2_CONFIG (1 + the fused kernel's configuration)
+    int force_k1_rows, force_gemm_tile, force_k2_config;
     wq_layout_t lay;
     std::atomic<int> prepared;
 };

@@ -464,7 +464,7 @@ template <int M>
 hipError_t launch_input_m(const wq_plan *p, hipStream_t s, const float *x, int8_t *Xq, float *sX) {
     constexpr int n = M + 2;
     int tr = tap_rows_per_wg(n, (long)(p->T_pad / 16) * (p->Cin / 32) * 4);
-    if (const char *e = getenv("WQ_K1_ROWS")) tr = atoi(e);   // for sweeps: n, n/2, 2 or 1
+    if (p->force_k1_rows > 0) tr = p->force_k1_rows;   // for sweeps: n, n/2, 2 or 1
     if (tr == n) return launch_input_rows<M, n>(p, s, x, Xq, sX);
     if (tr == 1) return launch_input_rows<M, 1>(p, s, x, Xq, sX);
     if (tr == 2) return launch_input_rows<M, 2>(p, s, x, Xq, sX);

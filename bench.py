@@ -28,6 +28,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 INT8_PEAK_TOPS = 5000.0        # MI355X published dense int8 MFMA rate
+VALU_PEAK_OPS = 256 * 64 * 2.4e9   # fp32 vector operations per second without packed math: 256 CUs x 4 SIMDs x 16 lanes
 
 
 def k1_bytes(lay):
@@ -266,6 +267,11 @@ def main():
             k2_hbm_frac=round(k2_bytes(lay) / (k2_us[k] * 1e-6) / 1e9 / HBM_PEAK_GBS, 3),
             k2_mfma_frac=round(2 * lay.n ** 2 * lay.tiles * lay.Cin * lay.Cout
                                / (k2_us[k] * 1e-6) / 1e12 / INT8_PEAK_TOPS, 4),
+            # the ceilings of stages 2+3: bytes, MFMA work, and the plain-ALU work the method
+            # forces (3 fp32 vector operations per output element, tap and group for the
+            # dequantization, unpacked: 256 CUs x 64 lanes x 2.4 GHz), each as time / measured time
+            k2_valu_frac=round(3 * lay.n ** 2 * lay.tiles * (lay.Cin // lay.group_size) * lay.Cout
+                               / (k2_us[k] * 1e-6) / VALU_PEAK_OPS, 4),
             k2_kernels=it["plan"].layout.k2_kernels, k3_us=round(k3_us[k], 2),
             k3_hbm_frac=round(k3_bytes(lay) / (k3_us[k] * 1e-6) / 1e9 / HBM_PEAK_GBS, 3)))
 

@@ -277,3 +277,29 @@ def test_two_kernel_form_with_more_than_65535_tiles(wq):
     if "WQ_K2_PATH" not in os.environ:
         assert wq.Plan(32, 112, 112, 128, 32, 2, 128).layout.k2_kernels == 2
     check(wq, d, want_P=False)
+
+
+def test_two_plans_on_two_streams_at_once(wq):
+    """The library keeps no state outside plans, blobs and workspaces: two layers enqueued on two
+    streams at the same time, many times over, give the results of running them one by one."""
+    cases = [workloads.small_layer(91, 2, 13, 11, 64, 48, 6, 32), workloads.small_layer(92, 1, 16, 16, 256, 64, 4, 64)]
+    ctx = []
+    for d in cases:
+        lay = d.layer
+        plan = wq.Plan(lay.N, lay.H, lay.W, lay.Cin, lay.Cout, lay.m, lay.group_size)
+        blob, ws, y = plan.alloc_blob(), plan.alloc_workspace(), plan.alloc_output()
+        x = torch.from_numpy(d.x).cuda()
+        plan.weight_prepare(torch.from_numpy(d.w).cuda(), torch.from_numpy(d.bias).cuda(), blob)
+        plan.forward(x, blob, ws, y)
+        torch.cuda.synchronize()
+        ctx.append(dict(plan=plan, blob=blob, ws=ws, y=y, x=x, want=y.clone(), stream=torch.cuda.Stream()))
+    for rep in range(20):
+        for c in ctx:
+            c["y"].fill_(float("nan"))
+        torch.cuda.synchronize()
+        for c in ctx:
+            with torch.cuda.stream(c["stream"]):
+                c["plan"].forward(c["x"], c["blob"], c["ws"], c["y"])
+        torch.cuda.synchronize()
+        for c in ctx:
+            assert torch.equal(c["y"], c["want"]), f"repetition {rep}"

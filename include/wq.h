@@ -19,9 +19,11 @@
  *     device memory, never synchronises, and enqueues all work on the
  *     hipStream_t passed as `stream` (NULL = the default stream).
  *   - `*_dev` pointers are device pointers; everything else is host memory.
- *   - All functions return a wq_status_t; no exceptions, no global state.
- *     Distinct plans may be used from distinct threads.  Every argument check
- *     happens on the host before any kernel is launched.
+ *   - All functions return a wq_status_t; no exceptions.  The library keeps no
+ *     state outside the objects it hands out and reads no environment
+ *     variable (the one exception, wq_conv_forward_static, says so).  Distinct
+ *     plans may be used from distinct threads.  Every argument check happens
+ *     on the host before any kernel is launched.
  *   - Inputs containing NaN/Inf give unspecified outputs.
  */
 #ifndef WQ_H
@@ -30,6 +32,9 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#if defined(__GNUC__)
+#pragma GCC visibility push(default)   /* the library itself is built with hidden visibility */
+#endif
 #ifdef __cplusplus
 extern "C" {
 #endif
@@ -38,9 +43,13 @@ typedef enum {
     WQ_OK = 0,
     WQ_ERR_INVALID_ARG = 1,   /* NULL pointer, non-positive size, Cin % group_size != 0 */
     WQ_ERR_UNSUPPORTED = 2,   /* m not in {2,4,6}; group_size not in {32,64,128,256,512};
-                                 a tensor of 2 GiB or more (input: more than 1 GiB) */
+                                 a tensor of 2 GiB or more (input: more than 1 GiB); a tuning
+                                 choice that does not apply to the plan's shape */
     WQ_ERR_BAD_TRANSFORM = 3, /* matrices non-finite or not a valid F(m,3) triple */
-    WQ_ERR_NOT_PREPARED = 4,  /* forward called on a plan that never prepared weights */
+    WQ_ERR_NOT_PREPARED = 4,  /* forward called on a plan that never prepared weights (tracked per
+                                 plan, not per blob: passing a blob that no wq_weight_prepare call
+                                 of an identical plan has filled is the caller's error and is not
+                                 detected) */
     WQ_ERR_WORKSPACE = 5,     /* a caller buffer is smaller than wq_plan_layout reports */
     WQ_ERR_DEVICE = 6         /* a kernel launch failed */
 } wq_status_t;
@@ -66,6 +75,8 @@ typedef struct {
     int32_t N, H, W, Cin, Cout, m, n, group_size, groups;
     int32_t TH, TW, T, T_pad, Cout_pad, kstep;
     int32_t k2_kernels; /* launches of wq_contract_output: 1 = fused kernel, 2 = GEMM + output transform */
+    int32_t k2_variant; /* which kernel instance stages 2+3 run, a wq_k2_variant_t (see wq_plan_tune) */
+    int32_t k1_rows;    /* tap rows per workgroup of the input kernel: n, n/2, 2 or 1 */
     uint64_t blob_bytes, blob_Wq_off, blob_sW_off, blob_bias_off;
     uint64_t ws_bytes, ws_Xq_off, ws_sX_off, ws_M_off;
     uint64_t debug_P_bytes;
@@ -76,6 +87,17 @@ typedef struct {
  * 0, 1, -1, infinity for m = 2), row-major fp64, host memory:
  * BT n*n, G n*3, AT m*n.  Any output pointer may be NULL. */
 wq_status_t wq_standard_transforms(int m, double *BT, double *G, double *AT);
+
+/* The scale-parametrised transforms of Section "Learnable Winograd transform
+ * scales" (W = S_G V_G w V_G^T S_G, X = S_B V_B x V_B^T S_B, y = V_A S_A Y S_A V_A^T
+ * with S_A S_B S_G = I): row i of the standard B^T times u_B[i], row i of the
+ * standard G times u_G[i], column i of the standard A^T divided by
+ * u_B[i]*u_G[i].  u_B, u_G: n finite non-zero host doubles each (else
+ * INVALID_ARG).  Outputs are host, row-major fp32 (BT n*n, G n*3, AT m*n),
+ * formed in fp64 and rounded once; any output pointer may be NULL.  The result
+ * is what wq_plan_create expects. */
+wq_status_t wq_scaled_transforms(int m, const double *u_B, const double *u_G,
+                                 float *BT, float *G, float *AT);
 
 /* Create a plan for one layer shape.  BT (n*n), G (n*3), AT (m*n) are host,
  * row-major fp32: the transform matrices WITH any learned diagonal scales
@@ -91,6 +113,44 @@ wq_status_t wq_plan_create(wq_plan_t **out, int N, int H, int W, int Cin, int Co
 wq_status_t wq_plan_destroy(wq_plan_t *plan);
 
 wq_status_t wq_plan_layout(const wq_plan_t *plan, wq_layout_t *out);
+
+/* Which kernel instance runs stages 2+3 (wq_layout_t::k2_variant).  The plan
+ * picks one from the layer shape; wq_plan_tune overrides the pick.
+ *   FUSED_*   one kernel, a wave per tap row, operands straight from L2 into
+ *             registers, output transform behind the contraction
+ *             (16x16 / 16x16 with K split over two waves / 32x16 / 32x32 register tiles);
+ *   GEMM_*    a tiled GEMM per tap that writes the fp32 Winograd-domain products to
+ *             the workspace (tiles x channels per workgroup), then an output-transform kernel;
+ *   LDS_FULL_* one kernel, every wave of a workgroup on the same tap, operand tiles staged
+ *             once per K-step in LDS and shared, the output transform accumulated tap row
+ *             by tap row in registers (tiles x channels per workgroup);
+ *   LDS_ROW_*  one workgroup per (tile block, channel block, tap row): the same staged
+ *             contraction over the n taps of a row folded into row sums of Y A, which go
+ *             to the workspace; a small second kernel applies A^T and the bias. */
+typedef enum {
+    WQ_K2_AUTO = -1,
+    WQ_K2_FUSED_16x16 = 0,
+    WQ_K2_FUSED_KSPLIT = 1,
+    WQ_K2_FUSED_32x16 = 2,
+    WQ_K2_FUSED_32x32 = 3,
+    WQ_K2_GEMM_64x64 = 10,
+    WQ_K2_GEMM_32x128 = 11,
+    WQ_K2_GEMM_128x128 = 12,
+    WQ_K2_LDS_FULL_64x64 = 20,
+    WQ_K2_LDS_FULL_32x64 = 21,
+    WQ_K2_LDS_ROW_64x64 = 30,
+    WQ_K2_LDS_ROW_32x64 = 31
+} wq_k2_variant_t;
+
+/* Tuning overrides (tests and sweeps; results stay within the documented
+ * bounds: int8 codes, scales and int32 sums do not depend on them, the fp32
+ * output only through its summation order).  Buffer sizes do not change.
+ *   k1_rows    tap rows per workgroup of the input kernel: 0 = the plan's
+ *              own choice, else one of 1, 2, n/2, n;
+ *   k2_variant WQ_K2_AUTO = the plan's own choice, else a wq_k2_variant_t.
+ * A value that is not listed -> INVALID_ARG; one that does not apply to this
+ * plan's shape, group size or matrices -> UNSUPPORTED (the plan is unchanged). */
+wq_status_t wq_plan_tune(wq_plan_t *plan, int k1_rows, int k2_variant);
 
 /* Offline stage (W = G w G^T, then group-wise quantization along Cin):
  * reads w_dev [Cout][Cin][3][3] fp32 and bias_dev [Cout] fp32 (NULL = zero
@@ -112,14 +172,24 @@ wq_status_t wq_contract_output(const wq_plan_t *plan, void *stream,
                                void *workspace_dev, size_t workspace_bytes,
                                const void *weight_blob_dev, size_t blob_bytes, float *y_dev);
 
+/* For profilers: only the first (part = 1) or only the second (part = 2) kernel of
+ * wq_contract_output (k2_kernels says how many there are; part 2 of a one-kernel variant
+ * launches nothing).  Any other part -> INVALID_ARG. */
+wq_status_t wq_contract_output_part(const wq_plan_t *plan, void *stream, void *workspace_dev,
+                                    size_t workspace_bytes, const void *weight_blob_dev,
+                                    size_t blob_bytes, float *y_dev, int part);
+
 /* Stage 2 alone, in the two-kernel form (any plan may call it, whatever
  * k2_kernels says): the n*n int8 GEMMs over the workspace's Xq/sX and the
- * blob's Wq/sW with per-group dequantization (the paper's Eq. 5 with the
- * scales of Eq. 15); writes M fp32 [T_pad][n*n][Cout_pad] at ws_M_off. */
+ * blob's Wq/sW with per-group dequantization (the Hadamard-product equation
+ * of Section "Winograd convolution" summed over input channels, with the scales of the
+ * second quantized-stage equation of Section "Learnable Winograd transform
+ * scales"); writes M fp32 [T_pad][n*n][Cout_pad] at ws_M_off. */
 wq_status_t wq_contract(const wq_plan_t *plan, void *stream, void *workspace_dev,
                         size_t workspace_bytes, const void *weight_blob_dev, size_t blob_bytes);
 
-/* Stage 3 alone (the paper's Eq. 6): y = A^T M A + bias from the M that
+/* Stage 3 alone (the output-transform equation of Section "Winograd
+ * convolution"): y = A^T M A + bias from the M that
  * wq_contract left in the workspace; writes y_dev [N][H][W][Cout] fp32. */
 wq_status_t wq_output_transform(const wq_plan_t *plan, void *stream, const void *workspace_dev,
                                 size_t workspace_bytes, const void *weight_blob_dev,
@@ -130,13 +200,29 @@ wq_status_t wq_conv_forward(const wq_plan_t *plan, void *stream, const float *x_
                             const void *weight_blob_dev, size_t blob_bytes,
                             void *workspace_dev, size_t workspace_bytes, float *y_dev);
 
-/* Same kernels as wq_conv_forward; additionally stores the exact int32 group
- * partial sums P[t][tile][group][o] = sum_{c in group} Xq*Wq to P_dev
- * (debug_P_bytes).  For tests. */
+/* wq_conv_forward with a dump of the exact int32 group partial sums
+ * P[t][tile][group][o] = sum_{c in group} Xq[t][tile][c] * Wq[t][o][c] (the
+ * integer product inside the second quantized-stage equation of Section
+ * "Learnable Winograd transform scales").  It launches exactly the kernel
+ * instances wq_conv_forward launches for this plan (wq_layout_t::k2_variant,
+ * same tile configuration, same launch shape), compiled from the same kernel
+ * templates with the stores of P switched on.
+ * P_dev: int32 [n*n][T][groups][Cout], dense (debug_P_bytes).  For tests. */
 wq_status_t wq_conv_forward_debug(const wq_plan_t *plan, void *stream, const float *x_dev,
                                   const void *weight_blob_dev, size_t blob_bytes,
                                   void *workspace_dev, size_t workspace_bytes, float *y_dev,
                                   int32_t *P_dev, size_t P_bytes);
+
+/* The same with only a slab of P stored, for layers whose full P is too large
+ * to keep: taps [tap0, tap0+ntaps) x tiles [tile0, tile0+ntiles), every group
+ * and output channel.  P_dev: int32 [ntaps][ntiles][groups][Cout]
+ * (ntaps*ntiles*groups*Cout*4 bytes, else WORKSPACE).  An empty or out-of-range
+ * slab -> INVALID_ARG. */
+wq_status_t wq_conv_forward_debug_slab(const wq_plan_t *plan, void *stream, const float *x_dev,
+                                       const void *weight_blob_dev, size_t blob_bytes,
+                                       void *workspace_dev, size_t workspace_bytes, float *y_dev,
+                                       int32_t *P_dev, size_t P_bytes,
+                                       int tap0, int ntaps, int tile0, int ntiles);
 
 /* ---------------------------------------------------------------------------
  * The group-wise int8 quantized STANDARD 3x3 convolution (stride 1, zero pad 1)
@@ -196,6 +282,11 @@ wq_status_t wq_direct_plan_create_bits(wq_direct_plan_t **out, int N, int H, int
                                        int group_size, int weight_bits);
 wq_status_t wq_linear_plan_create_bits(wq_direct_plan_t **out, int R, int Cin, int Cout, int group_size,
                                        int weight_bits);
+/* Tuning override for tests and sweeps: the number of workgroups that share the reduction of
+ * an output tile (wq_direct_layout_t::splits).  0 keeps the plan's own choice; a 3x3 plan takes
+ * 1, 3 or 9, a linear plan a power of two up to 16 that divides its group count; anything else
+ * -> UNSUPPORTED.  Changes ws_bytes: call it before sizing the workspace. */
+wq_status_t wq_direct_plan_tune(wq_direct_plan_t *plan, int splits);
 wq_status_t wq_direct_plan_destroy(wq_direct_plan_t *plan);
 wq_status_t wq_direct_plan_layout(const wq_direct_plan_t *plan, wq_direct_layout_t *out);
 
@@ -219,9 +310,28 @@ wq_status_t wq_direct_forward(const wq_direct_plan_t *plan, void *stream, const 
                               const void *weight_blob_dev, size_t blob_bytes, void *workspace_dev,
                               size_t workspace_bytes, float *y_dev);
 
+/* Issue-rate microbenchmark of the contraction's inner loop, without memory traffic: every
+ * wave repeats, `iters` times (even), the int8 MFMAs of one quantization group on
+ * `blocks_per_wave` (2 or 4) 16x16 blocks followed by the per-group dequantization the second
+ * quantized-stage equation of Section "Learnable Winograd transform scales" demands
+ * (M += float(P) * sW * sX: 12 vector instructions per block).  mode 0 = MFMAs only, 1 =
+ * dequantization only, 2 = each group's MFMAs then its dequantization, 3 = the MFMAs of the next
+ * group issued before the dequantization of the previous one.  group_size in {32,64,128,256,512}
+ * (32: the 16x16x32 instruction; otherwise group_size/64 16x16x64 instructions per block and
+ * group).  `workgroups` workgroups of 4 waves are launched.  seed_dev: 64 int32 (any values);
+ * out_dev: workgroups*256 floats (written so that nothing is optimised away); cycles_dev: two
+ * int64 per workgroup, the cycle-counter ticks and the 100 MHz wall-clock ticks its first wave
+ * spent in the loop. */
+wq_status_t wq_microbench_dequant(void *stream, int mode, int group_size, int blocks_per_wave,
+                                  int workgroups, int iters, const int32_t *seed_dev,
+                                  float *out_dev, long long *cycles_dev);
+
 const char *wq_status_string(wq_status_t status);
 
 #ifdef __cplusplus
 }
+#endif
+#if defined(__GNUC__)
+#pragma GCC visibility pop
 #endif
 #endif /* WQ_H */

@@ -30,7 +30,7 @@
 
 #include "wq_internal.h"
 
-namespace wq_k2 {
+namespace {   // every including file instantiates its own tile size; nothing here is exported
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v2i __attribute__((ext_vector_type(2)));
@@ -50,7 +50,7 @@ struct Args {
     const float *sW;
     const float *bias;
     float *y;
-    int32_t *P;
+    wq_dump dump;   // debug calls: where to store the int32 group sums (P == nullptr otherwise)
     int H, W, Cin, Cout, TH, TW, T, T_pad, Cout_pad, log2g;
     int nTB, nOB, xcd_mode;
 };
@@ -238,18 +238,12 @@ __global__ __launch_bounds__(64 * (M + 2) * KS) void k_contract_output(const Arg
                             Mc[no][nt].y = __builtin_fmaf((float)acc[no][nt][1], c[no][nt].y, Mc[no][nt].y);
                             Mc[no][nt].z = __builtin_fmaf((float)acc[no][nt][2], c[no][nt].z, Mc[no][nt].z);
                             Mc[no][nt].w = __builtin_fmaf((float)acc[no][nt][3], c[no][nt].w, Mc[no][nt].w);
-                            if constexpr (DUMP) {
-                                const int tau = tau0 + nt * 16 + l16;
-                                const int t = i * n + j_cp;
-                                if (tau < a.T) {
-#pragma unroll
-                                    for (int r = 0; r < 4; ++r) {
-                                        const int o = o0 + no * 16 + 4 * q + r;
-                                        if (o < a.Cout)
-                                            a.P[(((size_t)t * a.T + tau) * groups + ks * gps + gam_cp) *
-                                                    a.Cout + o] = acc[no][nt][r];
-                                    }
-                                }
+                            if constexpr (DUMP) {   // the debug entry point's instance of this kernel
+                                const int v[4] = {acc[no][nt][0], acc[no][nt][1], acc[no][nt][2],
+                                                  acc[no][nt][3]};
+                                wq_dump_store(a.dump, i * n + j_cp, tau0 + nt * 16 + l16,
+                                              ks * gps + gam_cp, groups, o0 + no * 16 + 4 * q, a.Cout,
+                                              a.T, v);
                             }
                             if constexpr (!CPG1) acc[no][nt] = v4i{0, 0, 0, 0};
                         }
@@ -367,11 +361,9 @@ __global__ __launch_bounds__(64 * (M + 2) * KS) void k_contract_output(const Arg
             }
 }
 
-// Tile configurations the launcher may pick (NT, NO, KS, prefetch depth)
-enum { CFG_BASE = 0, CFG_KSPLIT = 1, CFG_TALL = 2, CFG_BIG = 3 };
-
-template <int M, bool K64, bool CPG1, bool WIDE, bool ATSP, bool DUMP, int NT, int NO, int KS, int D>
+template <int M, bool K64, bool CPG1, bool WIDE, bool ATSP, int NT, int NO, int KS, int D>
 hipError_t launch_cfg(const Args &a, hipStream_t s) {
+    // the debug entry point runs the same template with the stores of the int32 sums compiled in
     Args b = a;
     b.nTB = a.T_pad / (16 * NT);
     b.nOB = a.Cout_pad / (16 * NO);
@@ -380,69 +372,53 @@ hipError_t launch_cfg(const Args &a, hipStream_t s) {
     b.xcd_mode = wbytes >= xbytes ? 0 : 1;
     const int split = b.xcd_mode == 0 ? b.nOB : b.nTB, other = b.xcd_mode == 0 ? b.nTB : b.nOB;
     const unsigned grid = (unsigned)(((split + 7) / 8) * 8 * other);
-    hipLaunchKernelGGL((k_contract_output<M, K64, CPG1, WIDE, ATSP, DUMP, NT, NO, KS, D>), dim3(grid),
-                       dim3(64 * (M + 2) * KS), 0, s, b);
+    if (a.dump.P)
+        hipLaunchKernelGGL((k_contract_output<M, K64, CPG1, WIDE, ATSP, true, NT, NO, KS, D>), dim3(grid),
+                           dim3(64 * (M + 2) * KS), 0, s, b);
+    else
+        hipLaunchKernelGGL((k_contract_output<M, K64, CPG1, WIDE, ATSP, false, NT, NO, KS, D>), dim3(grid),
+                           dim3(64 * (M + 2) * KS), 0, s, b);
     return hipGetLastError();
-}
-
-// Pick a tile configuration from the problem size.
-inline int choose_cfg(const wq_plan *p) {
-    if (!p->sparse_at || p->m == 2 || p->g > 64) return CFG_BASE;
-    // tuning knob: WQ_K2_CONFIG=0..3 forces a configuration where it is applicable
-    if (p->force_k2_config > 0) {
-        const int c = p->force_k2_config - 1;
-        if (c == CFG_KSPLIT && p->groups % 2 != 0) return CFG_BASE;
-        if (c >= CFG_BASE && c <= CFG_BIG) return c;
-    }
-    // Measured on MI355X over the ResNet / UNet layer shapes (tile blocks tb, channel blocks ob):
-    // few tile blocks -> split K over more waves; many blocks -> taller or bigger register tiles.
-    const long tb = p->T_pad / 16, ob = p->Cout_pad / 16;
-    const bool can_split = p->groups % 2 == 0 && p->groups >= 4;
-    if (tb <= 2) return can_split ? CFG_KSPLIT : CFG_BASE;
-    if (tb * ob >= 640) return ob >= 40 ? CFG_BIG : CFG_TALL;
-    if (tb >= 16) return CFG_TALL;
-    return (can_split && p->groups >= 16) ? CFG_KSPLIT : CFG_BASE;
 }
 
 // fp64 chunk totals only where a wave reduces more than 8 groups per tap
 template <int M, bool K64, bool CPG1, bool ATSP>
 hipError_t launch_base(const Args &a, hipStream_t s, bool wide) {
-    if (a.P)
-        return wide ? launch_cfg<M, K64, CPG1, true, ATSP, true, 1, 1, 1, WQ_D_BASE>(a, s)
-                    : launch_cfg<M, K64, CPG1, false, ATSP, true, 1, 1, 1, WQ_D_BASE>(a, s);
-    return wide ? launch_cfg<M, K64, CPG1, true, ATSP, false, 1, 1, 1, WQ_D_BASE>(a, s)
-                : launch_cfg<M, K64, CPG1, false, ATSP, false, 1, 1, 1, WQ_D_BASE>(a, s);
+    return wide ? launch_cfg<M, K64, CPG1, true, ATSP, 1, 1, 1, WQ_D_BASE>(a, s)
+                : launch_cfg<M, K64, CPG1, false, ATSP, 1, 1, 1, WQ_D_BASE>(a, s);
 }
 
+// the register-tile variants: one K-step per group, paired form of A^T
 template <int M, bool K64>
-hipError_t launch_fast(const Args &a, hipStream_t s, int cfg, bool wide) {
-    if (cfg == CFG_KSPLIT)
-        return wide ? launch_cfg<M, K64, true, true, true, false, 1, 1, 2, WQ_D_BASE>(a, s)
-                    : launch_cfg<M, K64, true, false, true, false, 1, 1, 2, WQ_D_BASE>(a, s);
-    if (cfg == CFG_TALL)
-        return wide ? launch_cfg<M, K64, true, true, true, false, 2, 1, 1, 3>(a, s)
-                    : launch_cfg<M, K64, true, false, true, false, 2, 1, 1, 3>(a, s);
-    return wide ? launch_cfg<M, K64, true, true, true, false, 2, 2, 1, 2>(a, s)
-                : launch_cfg<M, K64, true, false, true, false, 2, 2, 1, 2>(a, s);
+hipError_t launch_fast(const Args &a, hipStream_t s, int variant, bool wide) {
+    if (variant == WQ_K2_FUSED_KSPLIT)
+        return wide ? launch_cfg<M, K64, true, true, true, 1, 1, 2, WQ_D_BASE>(a, s)
+                    : launch_cfg<M, K64, true, false, true, 1, 1, 2, WQ_D_BASE>(a, s);
+    if (variant == WQ_K2_FUSED_32x16)
+        return wide ? launch_cfg<M, K64, true, true, true, 2, 1, 1, 3>(a, s)
+                    : launch_cfg<M, K64, true, false, true, 2, 1, 1, 3>(a, s);
+    return wide ? launch_cfg<M, K64, true, true, true, 2, 2, 1, 2>(a, s)
+                : launch_cfg<M, K64, true, false, true, 2, 2, 1, 2>(a, s);
 }
 
 template <int M>
 hipError_t launch_m(const wq_plan *p, hipStream_t s, const int8_t *Xq, const float *sX,
-                    const int8_t *Wq, const float *sW, const float *bias, float *y, int32_t *P) {
+                    const int8_t *Wq, const float *sW, const float *bias, float *y,
+                    const wq_dump &dump) {
     Args a;
     a.xf = p->xf;
-    a.Xq = Xq; a.sX = sX; a.Wq = Wq; a.sW = sW; a.bias = bias; a.y = y; a.P = P;
+    a.Xq = Xq; a.sX = sX; a.Wq = Wq; a.sW = sW; a.bias = bias; a.y = y; a.dump = dump;
     a.H = p->H; a.W = p->W; a.Cin = p->Cin; a.Cout = p->Cout; a.TH = p->TH; a.TW = p->TW;
     a.T = p->T; a.T_pad = p->T_pad; a.Cout_pad = p->Cout_pad;
     a.log2g = 0;
     while ((1 << a.log2g) < p->g) ++a.log2g;
     a.nTB = a.nOB = a.xcd_mode = 0;
     const bool k64 = p->kstep == 64, cpg1 = p->g == p->kstep;
-    const int cfg = P ? CFG_BASE : choose_cfg(p);
-    const bool wide = p->groups / (cfg == CFG_KSPLIT ? 2 : 1) > 8;
+    const int variant = p->k2_variant;   // a fused one, checked for this plan when it was chosen
+    const bool wide = p->groups / (variant == WQ_K2_FUSED_KSPLIT ? 2 : 1) > 8;
     if constexpr (M != 2) {
-        if (cfg != CFG_BASE)   // only reached with sparse_at and g in {32, 64}
-            return k64 ? launch_fast<M, true>(a, s, cfg, wide) : launch_fast<M, false>(a, s, cfg, wide);
+        if (variant != WQ_K2_FUSED_16x16)
+            return k64 ? launch_fast<M, true>(a, s, variant, wide) : launch_fast<M, false>(a, s, variant, wide);
     }
     if (!k64)
         return p->sparse_at ? launch_base<M, false, true, true>(a, s, wide)
@@ -454,4 +430,4 @@ hipError_t launch_m(const wq_plan *p, hipStream_t s, const int8_t *Xq, const flo
                         : launch_base<M, true, false, false>(a, s, wide);
 }
 
-}  // namespace wq_k2
+}  // namespace

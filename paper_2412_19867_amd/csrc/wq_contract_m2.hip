@@ -3,6 +3,6 @@
 
 hipError_t wq_launch_contract_m2(const wq_plan *p, hipStream_t s, const int8_t *Xq, const float *sX,
                                  const int8_t *Wq, const float *sW, const float *bias, float *y,
-                                 int32_t *P) {
-    return wq_k2::launch_m<2>(p, s, Xq, sX, Wq, sW, bias, y, P);
+                                 const wq_dump &dump) {
+    return launch_m<2>(p, s, Xq, sX, Wq, sW, bias, y, dump);
 }

@@ -412,11 +412,10 @@ static wq_status_t make_plan(wq_direct_plan_t **out, int N, int H, int W, int Ci
     w.N = N; w.H = H; w.W = W; w.Cin = Cin; w.Cout = Cout; w.m = 1; w.n = 3; w.g = group_size;
     w.groups = p->groups; w.TH = H; w.TW = W; w.T = (int)P; w.T_pad = (int)((P + 31) / 32 * 32);
     w.Cout_pad = p->Cout_pad; w.kstep = p->kstep; w.wbits = weight_bits;
-    w.force_k1_rows = w.force_gemm_tile = w.force_k2_config = 0;
+    w.k1_rows = 1; w.k2_variant = WQ_K2_FUSED_16x16;
     std::memset(&w.xf, 0, sizeof(w.xf));
     w.xf.G[0] = w.xf.G[4] = w.xf.G[8] = 1.0f;
     w.sparse_bt = w.sparse_g = w.sparse_at = false;
-    w.two_kernel = false;
     w.prepared.store(0);
     wq_direct_layout_t &L = p->lay;
     L.N = N; L.H = H; L.W = W; L.Cin = Cin; L.Cout = Cout; L.group_size = group_size;
@@ -434,10 +433,6 @@ static wq_status_t make_plan(wq_direct_plan_t **out, int N, int H, int W, int Ci
     // workspace, one more small kernel adds them) so that the chip has enough waves
     const long long base = ((P + 63) / 64) * ((Cp + 63) / 64);
     p->splits = base >= 512 ? 1 : (base * 3 >= 512 ? 3 : 9);
-    if (const char *e = std::getenv("WQ_DIRECT_SPLITS")) {
-        const int v = std::atoi(e);
-        if (v == 1 || v == 3 || v == 9) p->splits = v;
-    }
     if (taps == 1) {
         // a linear layer with few rows: split K, in whole groups, until the chip has enough
         // workgroups (the partial sums are added by the same small kernel)
@@ -445,10 +440,6 @@ static wq_status_t make_plan(wq_direct_plan_t **out, int N, int H, int W, int Ci
         while (base * p->splits < 512 && p->splits < 16 && p->groups % (p->splits * 2) == 0 &&
                Cin / (p->splits * 2) >= 256)
             p->splits *= 2;
-        if (const char *e = std::getenv("WQ_LINEAR_SPLITS")) {
-            const int v = std::atoi(e);
-            if (v >= 1 && v <= 16 && (v & (v - 1)) == 0 && p->groups % v == 0) p->splits = v;
-        }
     }
     L.splits = p->splits;
     L.ws_part_off = L.ws_sx_off + align256((uint64_t)P * p->groups * 4);
@@ -475,6 +466,21 @@ wq_status_t wq_linear_plan_create(wq_direct_plan_t **out, int R, int Cin, int Co
 wq_status_t wq_linear_plan_create_bits(wq_direct_plan_t **out, int R, int Cin, int Cout, int group_size,
                                        int weight_bits) {
     return make_plan(out, R, 1, 1, Cin, Cout, group_size, 1, weight_bits);
+}
+
+wq_status_t wq_direct_plan_tune(wq_direct_plan_t *plan, int splits) {
+    if (!plan || splits < 0) return WQ_ERR_INVALID_ARG;
+    if (splits == 0) return WQ_OK;
+    const bool ok = plan->taps == 9 ? (splits == 1 || splits == 3 || splits == 9)
+                                    : (splits <= 16 && (splits & (splits - 1)) == 0 &&
+                                       plan->groups % splits == 0);
+    if (!ok) return WQ_ERR_UNSUPPORTED;
+    plan->splits = splits;
+    wq_direct_layout_t &L = plan->lay;
+    L.splits = splits;
+    L.ws_bytes = L.ws_part_off +
+                 (splits > 1 ? align256((uint64_t)splits * plan->P * plan->Cout * 4) : 0);
+    return WQ_OK;
 }
 
 wq_status_t wq_direct_plan_destroy(wq_direct_plan_t *plan) {

@@ -37,7 +37,8 @@ struct GArgs {
     const int8_t *Wq;
     const float *sW;
     float *Mbuf;
-    int Cin, T_pad, Cout_pad, log2g, n2;
+    wq_dump dump;   // debug calls: where to store the int32 group sums (P == nullptr otherwise)
+    int Cin, T, Cout, T_pad, Cout_pad, log2g, n2;
     // workgroup tiles along channels and tiles, their product with the taps, and the share of
     // each XCD (set by the launcher)
     int nOBt, nTBt, total, per_xcd;
@@ -46,7 +47,7 @@ struct GArgs {
 
 // TBW = 16-tile blocks per workgroup (4: a 64x64 output tile, waves 2x2; 2: 32 tiles x 128
 // channels, waves 1x4, for layers whose padded tile count is an odd multiple of 32).
-template <bool K64, bool CPG1, bool WIDE, int TBW>
+template <bool K64, bool CPG1, bool WIDE, int TBW, bool DUMP>
 __global__ __launch_bounds__(256, 2) void k_gemm_dequant(const GArgs a) {
     constexpr int KSTEP = K64 ? 64 : 32, KB = KSTEP / 4;
     constexpr int BLK = 16 * KSTEP;              // bytes of one K-step of a 16-row block
@@ -159,16 +160,16 @@ __global__ __launch_bounds__(256, 2) void k_gemm_dequant(const GArgs a) {
     // few L2 channels; measured 4-7 % on layers with thousands of workgroups, nothing on
     // small ones).  The integer sums of a group do not depend on the order; the fp32 sum
     // over the groups is taken in the rotated order.
-    const int s0 = (logical % groups) * (cpg_mask + 1);
-    auto kpos = [&](int k) { const int v = k + s0; return v >= cps ? v - cps : v; };
+    const int k_rot = (logical % groups) * (cpg_mask + 1);
+    auto kpos = [&](int k) { const int v = k + k_rot; return v >= cps ? v - cps : v; };
 #pragma unroll
     for (int u = 0; u < PD; ++u) fetch(kpos(min(u, last)), pre[u], psc[u]);
     commit(0, pre[0], psc[0]);
     __syncthreads();
-    for (int s0 = 0; s0 < cps; s0 += PD) {
+    for (int sb = 0; sb < cps; sb += PD) {
 #pragma unroll
       for (int u = 0; u < PD; ++u) {
-        const int s = s0 + u;
+        const int s = sb + u;
         if (s >= cps) break;
         const int buf = u & 1;   // PD is even, so s & 1 == u & 1
         fetch(kpos(min(s + PD, last)), pre[u], psc[u]);   // slot u held step s, already in LDS
@@ -218,6 +219,12 @@ __global__ __launch_bounds__(256, 2) void k_gemm_dequant(const GArgs a) {
                     Mc[no][nt].y = __builtin_fmaf((float)acc[no][nt][1], sw.y * sx, Mc[no][nt].y);
                     Mc[no][nt].z = __builtin_fmaf((float)acc[no][nt][2], sw.z * sx, Mc[no][nt].z);
                     Mc[no][nt].w = __builtin_fmaf((float)acc[no][nt][3], sw.w * sx, Mc[no][nt].w);
+                    if constexpr (DUMP) {   // the debug entry point's instance of this kernel
+                        const int v[4] = {acc[no][nt][0], acc[no][nt][1], acc[no][nt][2], acc[no][nt][3]};
+                        wq_dump_store(a.dump, t, (tb0 + BM * wm + nt) * 16 + l16,
+                                      (kpos(s) * KSTEP) >> a.log2g, groups,
+                                      (ob0 + BN * wn + no) * 16 + 4 * q, a.Cout, a.T, v);
+                    }
                     if constexpr (!CPG1) acc[no][nt] = v4i{0, 0, 0, 0};
                 }
             }
@@ -324,6 +331,13 @@ __global__ __launch_bounds__(64 * M) void k_output_transform(const OArgs a) {
     }
 }
 
+// plain, or (debug entry point) the same kernel with the stores of the int32 sums compiled in
+template <bool K64, bool CPG1, bool WIDE, int TBW>
+void launch_one(dim3 grid, hipStream_t s, const GArgs &g) {
+    if (g.dump.P) hipLaunchKernelGGL((k_gemm_dequant<K64, CPG1, WIDE, TBW, true>), grid, dim3(256), 0, s, g);
+    else hipLaunchKernelGGL((k_gemm_dequant<K64, CPG1, WIDE, TBW, false>), grid, dim3(256), 0, s, g);
+}
+
 template <bool K64, bool CPG1>
 void launch_gemm(const GArgs &g0, hipStream_t s, bool wide, bool narrow, bool big) {
     GArgs g = g0;
@@ -337,22 +351,22 @@ void launch_gemm(const GArgs &g0, hipStream_t s, bool wide, bool narrow, bool bi
     if constexpr (K64 && !CPG1) {
         if (big && !wide) {
             const dim3 grid = shape(128, 128);
-            hipLaunchKernelGGL((k_gemm_dequant<true, false, false, 8>), grid, dim3(256), 0, s, g);
+            launch_one<true, false, false, 8>(grid, s, g);
             return;
         }
     }
     if (narrow) {
         const dim3 grid = shape(128, 32);
         if (wide)
-            hipLaunchKernelGGL((k_gemm_dequant<K64, CPG1, true, 2>), grid, dim3(256), 0, s, g);
+            launch_one<K64, CPG1, true, 2>(grid, s, g);
         else
-            hipLaunchKernelGGL((k_gemm_dequant<K64, CPG1, false, 2>), grid, dim3(256), 0, s, g);
+            launch_one<K64, CPG1, false, 2>(grid, s, g);
     } else {
         const dim3 grid = shape(64, 64);
         if (wide)
-            hipLaunchKernelGGL((k_gemm_dequant<K64, CPG1, true, 4>), grid, dim3(256), 0, s, g);
+            launch_one<K64, CPG1, true, 4>(grid, s, g);
         else
-            hipLaunchKernelGGL((k_gemm_dequant<K64, CPG1, false, 4>), grid, dim3(256), 0, s, g);
+            launch_one<K64, CPG1, false, 4>(grid, s, g);
     }
 }
 
@@ -368,23 +382,20 @@ void launch_out(const OArgs &o, dim3 grid, hipStream_t s, bool atsp) {
 
 hipError_t wq_launch_contract_unfused(const wq_plan *p, hipStream_t s, const int8_t *Xq, const float *sX,
                                       const int8_t *Wq, const float *sW, const float *bias, float *Mbuf,
-                                      float *y, int stages) {
+                                      float *y, int stages, const wq_dump &dump) {
     if (stages & 1) {
     GArgs g;
-    g.Xq = Xq; g.sX = sX; g.Wq = Wq; g.sW = sW; g.Mbuf = Mbuf;
-    g.Cin = p->Cin; g.T_pad = p->T_pad; g.Cout_pad = p->Cout_pad; g.n2 = p->n * p->n;
+    g.Xq = Xq; g.sX = sX; g.Wq = Wq; g.sW = sW; g.Mbuf = Mbuf; g.dump = dump;
+    g.Cin = p->Cin; g.T = p->T; g.Cout = p->Cout; g.T_pad = p->T_pad; g.Cout_pad = p->Cout_pad;
+    g.n2 = p->n * p->n;
     g.log2g = 0;
     while ((1 << g.log2g) < p->g) ++g.log2g;
     g.m_plain_stores = (long long)g.n2 * p->T_pad * p->Cout_pad * 4 > (128LL << 20);
     const bool k64 = p->kstep == 64, cpg1 = p->g == p->kstep, wide = p->groups > 8;
-    // 32-tile workgroups when the 64-tile ones would leave half a tile row of blocks empty
-    bool narrow = (p->T_pad % 64) == 32 && p->T_pad <= 160;
-    if (p->force_gemm_tile == 32) narrow = true;
-    if (p->force_gemm_tile == 64) narrow = false;
-    // 128x128 tiles: groups of 128 and more on layers with at least 1024 tiles and 256 channels
-    bool big = p->g >= 128 && p->T_pad >= 1024 && p->Cout_pad >= 256;
-    if (p->force_gemm_tile == 128) big = true;
-    if (p->force_gemm_tile == 32 || p->force_gemm_tile == 64) big = false;
+    // the tile shape is the plan's variant when that is one of this kernel's; a plan of another
+    // variant that calls this stage on its own (wq_contract) gets the 64x64 tiles
+    const bool narrow = p->k2_variant == WQ_K2_GEMM_32x128;
+    const bool big = p->k2_variant == WQ_K2_GEMM_128x128;
     if (!k64) launch_gemm<false, true>(g, s, wide, narrow, big);
     else if (cpg1) launch_gemm<true, true>(g, s, wide, narrow, big);
     else launch_gemm<true, false>(g, s, wide, narrow, big);

@@ -70,8 +70,11 @@ void detect_patterns(wq_plan *p) {
     for (int a = 0; a < M; ++a)
         for (int i = 0; i < n; ++i)
             if (!wq_pattern<M>::at(a, i) && p->xf.AT[a * n + i] != 0.0f) p->sparse_at = false;
-    // paired columns: AT[a][2k] = (-1)^a r_k AT[a][2k-1] within a few fp32 roundings (the entries
-    // of a rescaled matrix were rounded one by one)
+    // paired columns: AT[a][2k] = (-1)^a r_k AT[a][2k-1] to within one unit in the last place of
+    // fp32 (the entries of a rescaled matrix were rounded one by one, so exact equality is too
+    // much to ask; a difference of one ulp in a coefficient is of the size of the roundings the
+    // fp32 evaluation makes anyway).  Anything further off takes the dense code, which uses
+    // every entry as given.
     for (int k = 1; k <= (n - 2) / 2 && p->sparse_at; ++k) {
         const int i1 = 2 * k - 1, i2 = 2 * k;
         int best = 0;
@@ -83,7 +86,7 @@ void detect_patterns(wq_plan *p) {
         for (int a = 0; a < M; ++a) {
             const double want = ((a & 1) ? -1.0 : 1.0) * r * (double)p->xf.AT[a * n + i1];
             const double got = p->xf.AT[a * n + i2];
-            if (std::fabs(got - want) > 4.0 * 5.97e-8 * std::fabs(got) + 1e-37) p->sparse_at = false;
+            if (std::fabs(got - want) > 1.1920929e-7 * std::fabs(got) + 1e-37) p->sparse_at = false;
         }
         p->xf.ATr[k - 1] = (float)r;
     }
@@ -113,18 +116,89 @@ bool valid_triple(const wq_xf &xf, int m) {
     return true;
 }
 
-wq_status_t check_buffers(const wq_plan *p, const void *blob, size_t blob_bytes, const void *ws,
-                          size_t ws_bytes) {
+enum { CHECK_BLOB = 1, CHECK_WS = 2 };
+wq_status_t check_buffers(const wq_plan *p, int which, const void *blob, size_t blob_bytes,
+                          const void *ws, size_t ws_bytes) {
     if (!p) return WQ_ERR_INVALID_ARG;
-    if (blob_bytes != (size_t)-1) {
+    if (which & CHECK_BLOB) {
         if (!blob) return WQ_ERR_INVALID_ARG;
         if (blob_bytes < p->lay.blob_bytes) return WQ_ERR_WORKSPACE;
     }
-    if (ws_bytes != (size_t)-1) {
+    if (which & CHECK_WS) {
         if (!ws) return WQ_ERR_INVALID_ARG;
         if (ws_bytes < p->lay.ws_bytes) return WQ_ERR_WORKSPACE;
     }
     return WQ_OK;
+}
+
+// ---- which kernel instances a plan runs (all measured on MI355X) ----
+
+// Tap rows per workgroup of the input kernel.  A workgroup that forms all n rows reads its
+// tiles once and has the longest instruction stream per wave; splitting the rows over
+// blockIdx.y re-reads the tiles through L1/L2 but shortens the stream and multiplies the
+// waves.  Over layers from 32 to 20480 waves (counted with all rows in one workgroup): big
+// layers want all rows together, mid-sized ones halves, small ones two rows (one row only when
+// the layer is a handful of waves).
+int default_k1_rows(const wq_plan *p) {
+    const int n = p->n;
+    const long waves_all_rows = (long)(p->T_pad / 16) * (p->Cin / 32) * 4;
+    if (waves_all_rows >= 1536) return n;
+    if (n == 8 || waves_all_rows >= 1024) return n / 2;
+    if (waves_all_rows >= 128) return 2;
+    return 1;
+}
+
+bool k1_rows_ok(const wq_plan *p, int rows) {
+    return rows == 1 || rows == 2 || rows == p->n / 2 || rows == p->n;
+}
+
+bool variant_applicable(const wq_plan *p, int v) {
+    const bool fast_fused_ok = p->sparse_at && p->m != 2 && p->g <= 64;   // instantiated for one K-step per group
+    switch (v) {
+        case WQ_K2_FUSED_16x16: return true;
+        case WQ_K2_FUSED_KSPLIT: return fast_fused_ok && p->groups % 2 == 0;
+        case WQ_K2_FUSED_32x16:
+        case WQ_K2_FUSED_32x32: return fast_fused_ok;
+        case WQ_K2_GEMM_64x64:
+        case WQ_K2_GEMM_32x128: return true;
+        case WQ_K2_GEMM_128x128: return p->g >= 128 && p->groups <= 8;
+        case WQ_K2_LDS_FULL_64x64: return p->m == 4;   // 16 waves of F(6,3) state do not fit the registers
+        case WQ_K2_LDS_FULL_32x64:
+        case WQ_K2_LDS_ROW_64x64:
+        case WQ_K2_LDS_ROW_32x64: return p->m != 2;    // instantiated for F(4,3) and F(6,3)
+        default: return false;
+    }
+}
+
+int default_k2_variant(const wq_plan *p) {
+    // With few tiles the Winograd-domain result is small next to the operands, and a tiled GEMM
+    // per tap plus a separate output transform beats the fused kernel; so it does for very wide
+    // layers and for groups of 128 and more, where the fused kernel's register tiles re-read the
+    // operands too often.
+    const bool two_kernel = (p->T_pad <= 512 && (p->Cin >= 512 || (p->g == 32 && p->Cin >= 128))) ||
+                            p->Cin >= 1024 || p->g >= 128;
+    if (two_kernel) {
+        // 128x128 tiles: groups of 128 and more on layers with at least 1024 tiles and 256 channels
+        if (p->g >= 128 && p->groups <= 8 && p->T_pad >= 1024 && p->Cout_pad >= 256)
+            return WQ_K2_GEMM_128x128;
+        // 32-tile workgroups when 64-tile ones would leave half a tile row of blocks empty
+        if ((p->T_pad % 64) == 32 && p->T_pad <= 160) return WQ_K2_GEMM_32x128;
+        return WQ_K2_GEMM_64x64;
+    }
+    if (!variant_applicable(p, WQ_K2_FUSED_32x16)) return WQ_K2_FUSED_16x16;
+    // few tile blocks -> split K over more waves; many blocks -> taller or bigger register tiles
+    const long tb = p->T_pad / 16, ob = p->Cout_pad / 16;
+    const bool can_split = p->groups % 2 == 0 && p->groups >= 4;
+    if (tb <= 2) return can_split ? WQ_K2_FUSED_KSPLIT : WQ_K2_FUSED_16x16;
+    if (tb * ob >= 640) return ob >= 40 ? WQ_K2_FUSED_32x32 : WQ_K2_FUSED_32x16;
+    if (tb >= 16) return WQ_K2_FUSED_32x16;
+    return (can_split && p->groups >= 16) ? WQ_K2_FUSED_KSPLIT : WQ_K2_FUSED_16x16;
+}
+
+void publish_choices(wq_plan *p) {
+    p->lay.k2_variant = p->k2_variant;
+    p->lay.k1_rows = p->k1_rows;
+    p->lay.k2_kernels = (wq_is_gemm_variant(p->k2_variant) || wq_is_lds_row_variant(p->k2_variant)) ? 2 : 1;
 }
 
 struct Blob {
@@ -149,6 +223,29 @@ wq_status_t wq_standard_transforms(int m, double *BT, double *G, double *AT) {
     if (BT) std::memcpy(BT, bt, sizeof(double) * n * n);
     if (G) std::memcpy(G, g, sizeof(double) * n * 3);
     if (AT) std::memcpy(AT, at, sizeof(double) * m * n);
+    return WQ_OK;
+}
+
+wq_status_t wq_scaled_transforms(int m, const double *u_B, const double *u_G, float *BT, float *G,
+                                 float *AT) {
+    const double *bt, *g, *at;
+    if (!std_tables(m, &bt, &g, &at)) return WQ_ERR_UNSUPPORTED;
+    if (!u_B || !u_G) return WQ_ERR_INVALID_ARG;
+    const int n = m + 2;
+    for (int i = 0; i < n; ++i)
+        if (!std::isfinite(u_B[i]) || !std::isfinite(u_G[i]) || u_B[i] * u_G[i] == 0.0 ||
+            !std::isfinite(1.0 / (u_B[i] * u_G[i])))
+            return WQ_ERR_INVALID_ARG;
+    // S_B and S_G scale rows; S_A = (S_B S_G)^-1 scales the columns of A^T
+    if (BT)
+        for (int i = 0; i < n; ++i)
+            for (int k = 0; k < n; ++k) BT[i * n + k] = (float)(bt[i * n + k] * u_B[i]);
+    if (G)
+        for (int i = 0; i < n; ++i)
+            for (int k = 0; k < 3; ++k) G[i * 3 + k] = (float)(g[i * 3 + k] * u_G[i]);
+    if (AT)
+        for (int a = 0; a < m; ++a)
+            for (int i = 0; i < n; ++i) AT[a * n + i] = (float)(at[a * n + i] / (u_B[i] * u_G[i]));
     return WQ_OK;
 }
 
@@ -187,21 +284,6 @@ wq_status_t wq_plan_create(wq_plan_t **out, int N, int H, int W, int Cin, int Co
     p->Cout_pad = (Cout + 31) / 32 * 32;
     p->kstep = group_size == 32 ? 32 : 64;
     p->wbits = 8;
-    // Path for stages 2+3 (measured on MI355X): with few tiles the Winograd-domain result is
-    // small next to the operands, and a tiled GEMM per tap plus a separate output transform
-    // beats the fused kernel; so it does for very wide layers and for groups of 128 and more,
-    // where the fused kernel's register tiles re-read the operands too often.
-    // WQ_K2_PATH=fused|split overrides.
-    p->two_kernel = (p->T_pad <= 512 && (Cin >= 512 || (group_size == 32 && Cin >= 128))) ||
-                    Cin >= 1024 || group_size >= 128;
-    if (const char *e = std::getenv("WQ_K2_PATH")) {
-        if (!std::strcmp(e, "fused")) p->two_kernel = false;
-        if (!std::strcmp(e, "split")) p->two_kernel = true;
-    }
-    p->force_k1_rows = p->force_gemm_tile = p->force_k2_config = 0;
-    if (const char *e = std::getenv("WQ_K1_ROWS")) p->force_k1_rows = std::atoi(e);
-    if (const char *e = std::getenv("WQ_GEMM_TILE")) p->force_gemm_tile = std::atoi(e);
-    if (const char *e = std::getenv("WQ_K2_CONFIG")) p->force_k2_config = std::atoi(e) + 1;
     p->prepared.store(0);
     std::memset(&p->xf, 0, sizeof(p->xf));
     if (all) {
@@ -228,7 +310,6 @@ wq_status_t wq_plan_create(wq_plan_t **out, int N, int H, int W, int Cin, int Co
     L.group_size = group_size; L.groups = p->groups;
     L.TH = p->TH; L.TW = p->TW; L.T = p->T; L.T_pad = p->T_pad; L.Cout_pad = p->Cout_pad;
     L.kstep = p->kstep;
-    L.k2_kernels = p->two_kernel ? 2 : 1;
     const uint64_t n2 = (uint64_t)n * n;
     L.blob_Wq_off = 0;
     L.blob_sW_off = align256(n2 * p->Cout_pad * Cin);
@@ -239,6 +320,9 @@ wq_status_t wq_plan_create(wq_plan_t **out, int N, int H, int W, int Cin, int Co
     L.ws_M_off = L.ws_sX_off + align256(n2 * p->T_pad * p->groups * 4);
     L.ws_bytes = L.ws_M_off + align256(n2 * p->T_pad * p->Cout_pad * 4);
     L.debug_P_bytes = n2 * (uint64_t)T * p->groups * Cout * 4;
+    p->k1_rows = default_k1_rows(p);
+    p->k2_variant = default_k2_variant(p);
+    publish_choices(p);
     *out = p;
     return WQ_OK;
 }
@@ -246,6 +330,25 @@ wq_status_t wq_plan_create(wq_plan_t **out, int N, int H, int W, int Cin, int Co
 wq_status_t wq_plan_destroy(wq_plan_t *plan) {
     if (!plan) return WQ_ERR_INVALID_ARG;
     delete plan;
+    return WQ_OK;
+}
+
+wq_status_t wq_plan_tune(wq_plan_t *plan, int k1_rows, int k2_variant) {
+    if (!plan) return WQ_ERR_INVALID_ARG;
+    if (k1_rows < 0 || k1_rows > 8) return WQ_ERR_INVALID_ARG;
+    switch (k2_variant) {
+        case WQ_K2_AUTO:
+        case WQ_K2_FUSED_16x16: case WQ_K2_FUSED_KSPLIT: case WQ_K2_FUSED_32x16: case WQ_K2_FUSED_32x32:
+        case WQ_K2_GEMM_64x64: case WQ_K2_GEMM_32x128: case WQ_K2_GEMM_128x128:
+        case WQ_K2_LDS_FULL_64x64: case WQ_K2_LDS_FULL_32x64:
+        case WQ_K2_LDS_ROW_64x64: case WQ_K2_LDS_ROW_32x64: break;
+        default: return WQ_ERR_INVALID_ARG;
+    }
+    if (k1_rows != 0 && !k1_rows_ok(plan, k1_rows)) return WQ_ERR_UNSUPPORTED;
+    if (k2_variant != WQ_K2_AUTO && !variant_applicable(plan, k2_variant)) return WQ_ERR_UNSUPPORTED;
+    plan->k1_rows = k1_rows ? k1_rows : default_k1_rows(plan);
+    plan->k2_variant = k2_variant != WQ_K2_AUTO ? k2_variant : default_k2_variant(plan);
+    publish_choices(plan);
     return WQ_OK;
 }
 
@@ -258,7 +361,7 @@ wq_status_t wq_plan_layout(const wq_plan_t *plan, wq_layout_t *out) {
 wq_status_t wq_weight_prepare(wq_plan_t *plan, void *stream, const float *w_dev,
                               const float *bias_dev, void *weight_blob_dev, size_t blob_bytes) {
     if (!plan || !w_dev) return WQ_ERR_INVALID_ARG;
-    wq_status_t st = check_buffers(plan, weight_blob_dev, blob_bytes, nullptr, (size_t)-1);
+    wq_status_t st = check_buffers(plan, CHECK_BLOB, weight_blob_dev, blob_bytes, nullptr, 0);
     if (st != WQ_OK) return st;
     char *b = (char *)weight_blob_dev;
     hipError_t e = wq_launch_weight(plan, (hipStream_t)stream, w_dev, bias_dev,
@@ -273,7 +376,7 @@ wq_status_t wq_weight_prepare(wq_plan_t *plan, void *stream, const float *w_dev,
 wq_status_t wq_input_transform(const wq_plan_t *plan, void *stream, const float *x_dev,
                                void *workspace_dev, size_t workspace_bytes) {
     if (!plan || !x_dev) return WQ_ERR_INVALID_ARG;
-    wq_status_t st = check_buffers(plan, nullptr, (size_t)-1, workspace_dev, workspace_bytes);
+    wq_status_t st = check_buffers(plan, CHECK_WS, nullptr, 0, workspace_dev, workspace_bytes);
     if (st != WQ_OK) return st;
     char *ws = (char *)workspace_dev;
     hipError_t e = wq_launch_input(plan, (hipStream_t)stream, x_dev,
@@ -284,9 +387,9 @@ wq_status_t wq_input_transform(const wq_plan_t *plan, void *stream, const float 
 
 static wq_status_t contract_impl(const wq_plan_t *plan, void *stream, void *workspace_dev,
                                  size_t workspace_bytes, const void *weight_blob_dev,
-                                 size_t blob_bytes, float *y_dev, int32_t *P_dev) {
+                                 size_t blob_bytes, float *y_dev, const wq_dump &dump, int parts = 3) {
     if (!plan || !y_dev) return WQ_ERR_INVALID_ARG;
-    wq_status_t st = check_buffers(plan, weight_blob_dev, blob_bytes, workspace_dev, workspace_bytes);
+    wq_status_t st = check_buffers(plan, CHECK_BLOB | CHECK_WS, weight_blob_dev, blob_bytes, workspace_dev, workspace_bytes);
     if (st != WQ_OK) return st;
     if (!plan->prepared.load()) return WQ_ERR_NOT_PREPARED;
     char *ws = (char *)workspace_dev;
@@ -294,22 +397,32 @@ static wq_status_t contract_impl(const wq_plan_t *plan, void *stream, void *work
     hipError_t e = wq_launch_contract(plan, (hipStream_t)stream,
                                       (const int8_t *)(ws + plan->lay.ws_Xq_off),
                                       (const float *)(ws + plan->lay.ws_sX_off), bl.Wq, bl.sW,
-                                      bl.bias, (float *)(ws + plan->lay.ws_M_off), y_dev, P_dev);
+                                      bl.bias, (float *)(ws + plan->lay.ws_M_off), y_dev, dump, parts);
     return e == hipSuccess ? WQ_OK : WQ_ERR_DEVICE;
 }
+
+static const wq_dump kNoDump = {nullptr, 0, 0, 0, 0};
 
 wq_status_t wq_contract_output(const wq_plan_t *plan, void *stream, void *workspace_dev,
                                size_t workspace_bytes, const void *weight_blob_dev,
                                size_t blob_bytes, float *y_dev) {
     return contract_impl(plan, stream, workspace_dev, workspace_bytes, weight_blob_dev, blob_bytes,
-                         y_dev, nullptr);
+                         y_dev, kNoDump);
+}
+
+wq_status_t wq_contract_output_part(const wq_plan_t *plan, void *stream, void *workspace_dev,
+                                    size_t workspace_bytes, const void *weight_blob_dev,
+                                    size_t blob_bytes, float *y_dev, int part) {
+    if (part != 1 && part != 2) return WQ_ERR_INVALID_ARG;
+    return contract_impl(plan, stream, workspace_dev, workspace_bytes, weight_blob_dev, blob_bytes,
+                         y_dev, kNoDump, part);
 }
 
 static wq_status_t split_stage(const wq_plan_t *plan, void *stream, void *workspace_dev,
                                size_t workspace_bytes, const void *weight_blob_dev,
                                size_t blob_bytes, float *y_dev, int stages) {
     if (!plan || ((stages & 2) && !y_dev)) return WQ_ERR_INVALID_ARG;
-    wq_status_t st = check_buffers(plan, weight_blob_dev, blob_bytes, workspace_dev, workspace_bytes);
+    wq_status_t st = check_buffers(plan, CHECK_BLOB | CHECK_WS, weight_blob_dev, blob_bytes, workspace_dev, workspace_bytes);
     if (st != WQ_OK) return st;
     if (!plan->prepared.load()) return WQ_ERR_NOT_PREPARED;
     char *ws = (char *)workspace_dev;
@@ -318,7 +431,7 @@ static wq_status_t split_stage(const wq_plan_t *plan, void *stream, void *worksp
                                               (const int8_t *)(ws + plan->lay.ws_Xq_off),
                                               (const float *)(ws + plan->lay.ws_sX_off), bl.Wq,
                                               bl.sW, bl.bias, (float *)(ws + plan->lay.ws_M_off),
-                                              y_dev, stages);
+                                              y_dev, stages, kNoDump);
     return e == hipSuccess ? WQ_OK : WQ_ERR_DEVICE;
 }
 
@@ -339,28 +452,44 @@ wq_status_t wq_conv_forward(const wq_plan_t *plan, void *stream, const float *x_
                             const void *weight_blob_dev, size_t blob_bytes, void *workspace_dev,
                             size_t workspace_bytes, float *y_dev) {
     if (!plan || !x_dev || !y_dev) return WQ_ERR_INVALID_ARG;
-    wq_status_t st = check_buffers(plan, weight_blob_dev, blob_bytes, workspace_dev, workspace_bytes);
+    wq_status_t st = check_buffers(plan, CHECK_BLOB | CHECK_WS, weight_blob_dev, blob_bytes, workspace_dev, workspace_bytes);
     if (st != WQ_OK) return st;
     if (!plan->prepared.load()) return WQ_ERR_NOT_PREPARED;
     st = wq_input_transform(plan, stream, x_dev, workspace_dev, workspace_bytes);
     if (st != WQ_OK) return st;
     return contract_impl(plan, stream, workspace_dev, workspace_bytes, weight_blob_dev, blob_bytes,
-                         y_dev, nullptr);
+                         y_dev, kNoDump);
+}
+
+wq_status_t wq_conv_forward_debug_slab(const wq_plan_t *plan, void *stream, const float *x_dev,
+                                       const void *weight_blob_dev, size_t blob_bytes,
+                                       void *workspace_dev, size_t workspace_bytes, float *y_dev,
+                                       int32_t *P_dev, size_t P_bytes, int tap0, int ntaps, int tile0,
+                                       int ntiles) {
+    if (!plan || !x_dev || !y_dev || !P_dev) return WQ_ERR_INVALID_ARG;
+    wq_status_t st = check_buffers(plan, CHECK_BLOB | CHECK_WS, weight_blob_dev, blob_bytes, workspace_dev, workspace_bytes);
+    if (st != WQ_OK) return st;
+    const int n2 = plan->n * plan->n;
+    if (tap0 < 0 || ntaps <= 0 || tap0 > n2 - ntaps || tile0 < 0 || ntiles <= 0 ||
+        tile0 > plan->T - ntiles)
+        return WQ_ERR_INVALID_ARG;
+    if (P_bytes < (size_t)ntaps * ntiles * plan->groups * plan->Cout * 4) return WQ_ERR_WORKSPACE;
+    if (!plan->prepared.load()) return WQ_ERR_NOT_PREPARED;
+    st = wq_input_transform(plan, stream, x_dev, workspace_dev, workspace_bytes);
+    if (st != WQ_OK) return st;
+    const wq_dump dump = {P_dev, tap0, ntaps, tile0, ntiles};
+    return contract_impl(plan, stream, workspace_dev, workspace_bytes, weight_blob_dev, blob_bytes,
+                         y_dev, dump);
 }
 
 wq_status_t wq_conv_forward_debug(const wq_plan_t *plan, void *stream, const float *x_dev,
                                   const void *weight_blob_dev, size_t blob_bytes,
                                   void *workspace_dev, size_t workspace_bytes, float *y_dev,
                                   int32_t *P_dev, size_t P_bytes) {
-    if (!plan || !x_dev || !y_dev || !P_dev) return WQ_ERR_INVALID_ARG;
-    wq_status_t st = check_buffers(plan, weight_blob_dev, blob_bytes, workspace_dev, workspace_bytes);
-    if (st != WQ_OK) return st;
-    if (P_bytes < plan->lay.debug_P_bytes) return WQ_ERR_WORKSPACE;
-    if (!plan->prepared.load()) return WQ_ERR_NOT_PREPARED;
-    st = wq_input_transform(plan, stream, x_dev, workspace_dev, workspace_bytes);
-    if (st != WQ_OK) return st;
-    return contract_impl(plan, stream, workspace_dev, workspace_bytes, weight_blob_dev, blob_bytes,
-                         y_dev, P_dev);
+    if (!plan) return WQ_ERR_INVALID_ARG;
+    return wq_conv_forward_debug_slab(plan, stream, x_dev, weight_blob_dev, blob_bytes, workspace_dev,
+                                      workspace_bytes, y_dev, P_dev, P_bytes, 0, plan->n * plan->n, 0,
+                                      plan->T);
 }
 
 const char *wq_status_string(wq_status_t status) {

@@ -32,12 +32,9 @@ struct wq_plan {
     // sparse_at additionally requires the paired form of A^T (see wq_xf::ATr); matrices
     // without it take the dense output-transform code.
     bool sparse_bt, sparse_g, sparse_at;
-    // stages 2+3 as GEMM + separate output transform (few tiles, many channels) instead of fused
-    bool two_kernel;
-    // tuning overrides read from the environment once, when the plan is made (0 = the library's
-    // own choice): WQ_K1_ROWS (tap rows per workgroup of the input kernel), WQ_GEMM_TILE (32, 64
-    // or 128 tiles per workgroup of the tiled GEMM), WQ_K2_CONFIG (1 + the fused kernel's configuration)
-    int force_k1_rows, force_gemm_tile, force_k2_config;
+    // the kernel instance of stages 2+3 (a wq_k2_variant_t) and the tap rows per workgroup of the
+    // input kernel, picked from the shape when the plan is made (wq_plan_tune overrides them)
+    int k2_variant, k1_rows;
     wq_layout_t lay;
     std::atomic<int> prepared;
 };
@@ -82,6 +79,30 @@ __device__ __forceinline__ void wq_apply_at(const wq_xf &xf, const float (&v)[M 
     }
 }
 
+inline bool wq_is_gemm_variant(int v) { return v >= WQ_K2_GEMM_64x64 && v <= WQ_K2_GEMM_128x128; }
+inline bool wq_is_fused_variant(int v) { return v >= WQ_K2_FUSED_16x16 && v <= WQ_K2_FUSED_32x32; }
+inline bool wq_is_lds_full_variant(int v) { return v >= WQ_K2_LDS_FULL_64x64 && v <= WQ_K2_LDS_FULL_32x64; }
+inline bool wq_is_lds_row_variant(int v) { return v >= WQ_K2_LDS_ROW_64x64 && v <= WQ_K2_LDS_ROW_32x64; }
+
+// Which part of the int32 group sums a debug call stores: taps [tap0, tap0+ntaps) x tiles
+// [tile0, tile0+ntiles), P [ntaps][ntiles][groups][Cout].  P == nullptr: no dump.
+struct wq_dump {
+    int32_t *P;
+    int tap0, ntaps, tile0, ntiles;
+};
+
+// Store the 4 int32 sums a lane holds after an int8 MFMA block (output channels o..o+3 of
+// tile tau, tap t, group gam) into the dump slab.  Called under a uniform `if (d.P)`.
+__device__ __forceinline__ void wq_dump_store(const wq_dump &d, int t, int tau, int gam, int groups,
+                                              int o, int Cout, int T, const int (&v)[4]) {
+    const int tt = t - d.tap0, tl = tau - d.tile0;
+    if (tt < 0 || tt >= d.ntaps || tl < 0 || tl >= d.ntiles || tau >= T || gam < 0 || gam >= groups) return;
+    int32_t *dst = d.P + (((size_t)tt * d.ntiles + tl) * groups + gam) * (size_t)Cout;
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+        if (o + r < Cout) dst[o + r] = v[r];
+}
+
 // Kernel launchers (each enqueues on `s` and returns the launch status).
 hipError_t wq_launch_weight(const wq_plan *p, hipStream_t s, const float *w, const float *bias,
                             int8_t *Wq, float *sW, float *bias_out);
@@ -90,10 +111,17 @@ hipError_t wq_launch_weight_rows(const wq_plan *p, hipStream_t s, const float *w
                                  int8_t *Wq, float *sW, float *bias_out);
 hipError_t wq_launch_input(const wq_plan *p, hipStream_t s, const float *x, int8_t *Xq, float *sX);
 // Mbuf: fp32 scratch [T_pad][taps][Cout_pad] inside the workspace, used by the two-kernel path
+// parts: bit 0 = the first kernel of the plan's variant, bit 1 = its second kernel (if it has one)
 hipError_t wq_launch_contract(const wq_plan *p, hipStream_t s, const int8_t *Xq, const float *sX,
                               const int8_t *Wq, const float *sW, const float *bias, float *Mbuf,
-                              float *y, int32_t *P);
+                              float *y, const wq_dump &dump, int parts = 3);
 // stages: bit 0 = tiled GEMM with group dequantization into Mbuf, bit 1 = output transform of Mbuf
 hipError_t wq_launch_contract_unfused(const wq_plan *p, hipStream_t s, const int8_t *Xq,
                                       const float *sX, const int8_t *Wq, const float *sW,
-                                      const float *bias, float *Mbuf, float *y, int stages = 3);
+                                      const float *bias, float *Mbuf, float *y, int stages,
+                                      const wq_dump &dump);
+// the operand-staging (LDS) kernels: full fusion, or tap-row sums + finishing kernel (Mbuf holds
+// the row sums)
+hipError_t wq_launch_contract_lds(const wq_plan *p, hipStream_t s, const int8_t *Xq, const float *sX,
+                                  const int8_t *Wq, const float *sW, const float *bias, float *Mbuf,
+                                  float *y, const wq_dump &dump, int parts);

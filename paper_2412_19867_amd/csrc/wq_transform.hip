@@ -21,7 +21,7 @@
 // The input kernel can additionally split the n tap rows over blockIdx.y:
 // B^T d only has to be formed for the workgroup's rows, so the split costs
 // nothing but re-reading the tile through L1, and it cuts the registers and
-// the length of the per-wave instruction stream (see tap_rows_per_wg).
+// the length of the per-wave instruction stream (the plan's k1_rows).
 // The arithmetic order is part of the library's contract: the int8 codes and
 // scales are reproducible bit for bit from the definition in include/wq.h.
 #include <float.h>
@@ -179,19 +179,8 @@ __device__ __forceinline__ void quantize_and_store(const float2 (&vals)[NT], uin
 }
 
 // ---------------------------------------------------------------- stage 1
-// Tap rows per workgroup of the input kernel.  A workgroup that forms all n rows reads its
-// tiles once and has the longest instruction stream per wave; splitting the rows over
-// blockIdx.y re-reads the tiles through L1/L2 but shortens the stream and multiplies the
-// waves.  Measured over layers from 32 to 20480 waves (counted with all rows in one
-// workgroup): big layers want all rows together, mid-sized ones halves, small ones two
-// rows (one row only when the layer is a handful of waves).
-inline int tap_rows_per_wg(int n, long waves_all_rows) {
-    if (waves_all_rows >= 1536) return n;
-    if (n == 8 || waves_all_rows >= 1024) return n / 2;
-    if (waves_all_rows >= 128) return 2;
-    return 1;
-}
-
+// The tap rows per workgroup of the input kernel are the plan's k1_rows (chosen from the
+// layer's wave count when the plan is made).
 template <int M, int TR, int I0, bool SPARSE>
 __device__ __forceinline__ void input_body(const wq_xf &xf, const float *__restrict__ x,
                                            int8_t *__restrict__ Xq, float *__restrict__ sX, int H,
@@ -463,8 +452,7 @@ hipError_t launch_input_rows(const wq_plan *p, hipStream_t s, const float *x, in
 template <int M>
 hipError_t launch_input_m(const wq_plan *p, hipStream_t s, const float *x, int8_t *Xq, float *sX) {
     constexpr int n = M + 2;
-    int tr = tap_rows_per_wg(n, (long)(p->T_pad / 16) * (p->Cin / 32) * 4);
-    if (p->force_k1_rows > 0) tr = p->force_k1_rows;   // for sweeps: n, n/2, 2 or 1
+    const int tr = p->k1_rows;   // n, n/2, 2 or 1
     if (tr == n) return launch_input_rows<M, n>(p, s, x, Xq, sX);
     if (tr == 1) return launch_input_rows<M, 1>(p, s, x, Xq, sX);
     if (tr == 2) return launch_input_rows<M, 2>(p, s, x, Xq, sX);

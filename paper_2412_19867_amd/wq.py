@@ -19,7 +19,9 @@ STATUS_NAMES = {0: "WQ_OK", 1: "WQ_ERR_INVALID_ARG", 2: "WQ_ERR_UNSUPPORTED",
                 3: "WQ_ERR_BAD_TRANSFORM", 4: "WQ_ERR_NOT_PREPARED", 5: "WQ_ERR_WORKSPACE",
                 6: "WQ_ERR_DEVICE"}
 
-EXPORTS = ["wq_standard_transforms", "wq_plan_create", "wq_plan_destroy", "wq_plan_layout",
+EXPORTS = ["wq_standard_transforms", "wq_scaled_transforms", "wq_plan_create", "wq_plan_destroy",
+           "wq_plan_layout", "wq_plan_tune", "wq_conv_forward_debug_slab", "wq_direct_plan_tune",
+           "wq_contract_output_part", "wq_microbench_dequant",
            "wq_weight_prepare", "wq_input_transform", "wq_contract_output", "wq_contract",
            "wq_output_transform", "wq_conv_forward",
            "wq_direct_plan_create", "wq_linear_plan_create", "wq_direct_plan_create_bits",
@@ -31,7 +33,8 @@ EXPORTS = ["wq_standard_transforms", "wq_plan_create", "wq_plan_destroy", "wq_pl
 class Layout(ctypes.Structure):
     _fields_ = ([(k, ctypes.c_int32) for k in
                  ("N", "H", "W", "Cin", "Cout", "m", "n", "group_size", "groups",
-                  "TH", "TW", "T", "T_pad", "Cout_pad", "kstep", "k2_kernels")] +
+                  "TH", "TW", "T", "T_pad", "Cout_pad", "kstep", "k2_kernels", "k2_variant",
+                  "k1_rows")] +
                 [(k, ctypes.c_uint64) for k in
                  ("blob_bytes", "blob_Wq_off", "blob_sW_off", "blob_bias_off",
                   "ws_bytes", "ws_Xq_off", "ws_sX_off", "ws_M_off", "debug_P_bytes")])
@@ -44,6 +47,13 @@ class DirectLayout(ctypes.Structure):
                 [(k, ctypes.c_uint64) for k in
                  ("blob_bytes", "blob_Wq_off", "blob_sW_off", "blob_bias_off",
                   "ws_bytes", "ws_xq_off", "ws_sx_off", "ws_part_off")])
+
+
+# wq_k2_variant_t (include/wq.h): the kernel instance of stages 2+3
+K2_VARIANTS = {"auto": -1, "fused_16x16": 0, "fused_ksplit": 1, "fused_32x16": 2, "fused_32x32": 3,
+               "gemm_64x64": 10, "gemm_32x128": 11, "gemm_128x128": 12,
+               "lds_full_64x64": 20, "lds_full_32x64": 21, "lds_row_64x64": 30, "lds_row_32x64": 31}
+K2_VARIANT_NAMES = {v: k for k, v in K2_VARIANTS.items()}
 
 
 class WqError(RuntimeError):
@@ -65,13 +75,19 @@ def lib() -> ctypes.CDLL:
         L = ctypes.CDLL(LIB_PATH)
         vp, sz, ip = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
         L.wq_standard_transforms.argtypes = [ip, vp, vp, vp]
+        L.wq_scaled_transforms.argtypes = [ip, vp, vp, vp, vp, vp]
         L.wq_plan_create.argtypes = [ctypes.POINTER(vp), ip, ip, ip, ip, ip, ip, ip, vp, vp, vp]
+        L.wq_plan_tune.argtypes = [vp, ip, ip]
+        L.wq_conv_forward_debug_slab.argtypes = [vp, vp, vp, vp, sz, vp, sz, vp, vp, sz, ip, ip, ip, ip]
+        L.wq_direct_plan_tune.argtypes = [vp, ip]
         L.wq_plan_destroy.argtypes = [vp]
         L.wq_plan_layout.argtypes = [vp, ctypes.POINTER(Layout)]
         L.wq_weight_prepare.argtypes = [vp, vp, vp, vp, vp, sz]
         L.wq_input_transform.argtypes = [vp, vp, vp, vp, sz]
         L.wq_contract_output.argtypes = [vp, vp, vp, sz, vp, sz, vp]
+        L.wq_contract_output_part.argtypes = [vp, vp, vp, sz, vp, sz, vp, ip]
         L.wq_contract.argtypes = [vp, vp, vp, sz, vp, sz]
+        L.wq_microbench_dequant.argtypes = [vp, ip, ip, ip, ip, ip, vp, vp, vp]
         L.wq_output_transform.argtypes = [vp, vp, vp, sz, vp, sz, vp]
         L.wq_conv_forward.argtypes = [vp, vp, vp, vp, sz, vp, sz, vp]
         L.wq_conv_forward_debug.argtypes = [vp, vp, vp, vp, sz, vp, sz, vp, vp, sz]
@@ -113,19 +129,18 @@ def standard_transforms(m: int):
 
 
 def scaled_transforms(m: int, u_B, u_G):
-    """Apply learned diagonal scales to the standard matrices: rows of B^T by
-    u_B, rows of G by u_G, columns of A^T by 1/(u_B u_G), so that the product of
-    the three diagonal scale matrices stays the identity (Section "Learnable
-    Winograd transform scales").  fp64 in, rounded once to fp32 out."""
-    AT, BT, G = standard_transforms(m)
-    u_B, u_G = np.asarray(u_B, np.float64), np.asarray(u_G, np.float64)
-    if u_B.shape != (m + 2,) or u_G.shape != (m + 2,):
+    """(A^T, B^T, G) in fp32 with learned diagonal scales applied to the standard matrices
+    (wq_scaled_transforms: rows of B^T by u_B, rows of G by u_G, columns of A^T by
+    1/(u_B u_G))."""
+    n = m + 2
+    u_B, u_G = np.ascontiguousarray(u_B, np.float64), np.ascontiguousarray(u_G, np.float64)
+    if u_B.shape != (n,) or u_G.shape != (n,):
         raise ValueError("need one scale per row of B^T and of G")
-    if not (np.all(np.isfinite(u_B)) and np.all(np.isfinite(u_G)) and np.all(u_B * u_G != 0)):
-        raise ValueError("scales must be finite and non-zero")
-    return ((AT / (u_B * u_G)[None, :]).astype(np.float32),
-            (BT * u_B[:, None]).astype(np.float32),
-            (G * u_G[:, None]).astype(np.float32))
+    BT, G, AT = (np.empty((n, n), np.float32), np.empty((n, 3), np.float32),
+                 np.empty((m, n), np.float32))
+    _check(lib().wq_scaled_transforms(m, u_B.ctypes.data, u_G.ctypes.data, BT.ctypes.data,
+                                      G.ctypes.data, AT.ctypes.data), "wq_scaled_transforms")
+    return AT, BT, G
 
 
 def _stream_handle(stream) -> int:
@@ -170,6 +185,17 @@ class Plan:
         if h and _lib is not None:
             _lib.wq_plan_destroy(h)
             self._h = None
+
+    def tune(self, k1_rows: int = 0, k2_variant=-1):
+        """Override the plan's kernel choices (wq_plan_tune); k2_variant by number or name."""
+        v = K2_VARIANTS[k2_variant] if isinstance(k2_variant, str) else int(k2_variant)
+        _check(lib().wq_plan_tune(self._h, int(k1_rows), v), "wq_plan_tune")
+        _check(lib().wq_plan_layout(self._h, ctypes.byref(self.layout)), "wq_plan_layout")
+        return self
+
+    @property
+    def k2_variant_name(self) -> str:
+        return K2_VARIANT_NAMES.get(self.layout.k2_variant, str(self.layout.k2_variant))
 
     # ---- buffers (device memory comes from torch) ----
     def alloc_blob(self, device="cuda"):
@@ -258,6 +284,15 @@ class Plan:
                                         _dev_ptr(y, torch.float32, "y", L.N * L.H * L.W * L.Cout)),
                "wq_contract_output")
 
+    def contract_output_part(self, ws, blob, y, part, stream=None):
+        import torch
+        L = self.layout
+        _check(lib().wq_contract_output_part(self._h, _stream_handle(stream),
+                                             _dev_ptr(ws, torch.uint8, "workspace"), ws.numel(),
+                                             _dev_ptr(blob, torch.uint8, "blob"), blob.numel(),
+                                             _dev_ptr(y, torch.float32, "y", L.N * L.H * L.W * L.Cout), int(part)),
+               "wq_contract_output_part")
+
     def contract(self, ws, blob, stream=None):
         import torch
         _check(lib().wq_contract(self._h, _stream_handle(stream),
@@ -296,6 +331,39 @@ class Plan:
                "wq_conv_forward_debug")
 
 
+    def _forward_debug_slab(self, x, blob, ws, y, P, tap0, ntaps, tile0, ntiles, stream=None):
+        import torch
+        L = self.layout
+        _check(lib().wq_conv_forward_debug_slab(
+            self._h, _stream_handle(stream), _dev_ptr(x, torch.float32, "x", L.N * L.H * L.W * L.Cin),
+            _dev_ptr(blob, torch.uint8, "blob"), blob.numel(), _dev_ptr(ws, torch.uint8, "workspace"),
+            ws.numel(), _dev_ptr(y, torch.float32, "y", L.N * L.H * L.W * L.Cout),
+            _dev_ptr(P, torch.int32, "P"), P.numel() * 4, tap0, ntaps, tile0, ntiles),
+            "wq_conv_forward_debug_slab")
+
+    def forward_debug_slab(self, x, blob, ws, y, tap0, ntaps, tile0, ntiles, stream=None):
+        """Forward pass that also returns P[tap0:tap0+ntaps, tile0:tile0+ntiles] (int32 device tensor)."""
+        import torch
+        L = self.layout
+        P = torch.empty((ntaps, ntiles, L.groups, L.Cout), dtype=torch.int32, device=x.device)
+        self._forward_debug_slab(x, blob, ws, y, P, tap0, ntaps, tile0, ntiles, stream)
+        return P
+
+
+def microbench_dequant(mode: int, group_size: int, blocks_per_wave: int, workgroups: int, iters: int,
+                       stream=None):
+    """Runs wq_microbench_dequant once; returns the per-workgroup (cycle-counter, 100 MHz wall-clock)
+    tick counts of the loop as a [workgroups, 2] device tensor."""
+    import torch
+    seed = torch.arange(64, dtype=torch.int32, device="cuda")
+    out = torch.empty(workgroups * 256, dtype=torch.float32, device="cuda")
+    cyc = torch.zeros((workgroups, 2), dtype=torch.int64, device="cuda")
+    _check(lib().wq_microbench_dequant(_stream_handle(stream), mode, group_size, blocks_per_wave, workgroups,
+                                       iters, seed.data_ptr(), out.data_ptr(), cyc.data_ptr()),
+           "wq_microbench_dequant")
+    return cyc
+
+
 class DirectPlan:
     """The group-wise quantized standard 3x3 convolution (the paper's runtime
     comparison point) for one layer shape.  Owns only the host-side plan object."""
@@ -310,6 +378,12 @@ class DirectPlan:
                                                     weight_bits), "wq_direct_plan_create_bits")
         self.layout = DirectLayout()
         _check(lib().wq_direct_plan_layout(self._h, ctypes.byref(self.layout)), "wq_direct_plan_layout")
+
+    def tune(self, splits: int):
+        """Override how many workgroups share an output tile's reduction (wq_direct_plan_tune)."""
+        _check(lib().wq_direct_plan_tune(self._h, int(splits)), "wq_direct_plan_tune")
+        _check(lib().wq_direct_plan_layout(self._h, ctypes.byref(self.layout)), "wq_direct_plan_layout")
+        return self
 
     def __del__(self):
         h = getattr(self, "_h", None)

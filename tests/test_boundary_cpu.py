@@ -46,8 +46,69 @@ def test_scaled_transforms_match_the_oracle_parametrisation(wq):
             np.testing.assert_allclose(a, b, rtol=1.2e-7)
     with pytest.raises(ValueError):
         wq.scaled_transforms(4, np.ones(5), np.ones(6))
-    with pytest.raises(ValueError):
+    with pytest.raises(wq.WqError):
         wq.scaled_transforms(4, np.zeros(6), np.ones(6))
+    with pytest.raises(wq.WqError):
+        wq.scaled_transforms(4, np.full(6, np.inf), np.ones(6))
+    with pytest.raises(wq.WqError):
+        wq.scaled_transforms(5, np.ones(7), np.ones(7))
+    # the result is a valid triple for wq_plan_create, and the paper's learned F(6,3) scales are too
+    rng = np.random.default_rng(1)
+    AT, BT, G = wq.scaled_transforms(6, rng.uniform(0.5, 2, 8), rng.uniform(0.5, 2, 8))
+    wq.Plan(1, 8, 8, 32, 32, 6, 32, AT=AT, BT=BT, G=G)
+
+
+def test_only_the_c_abi_is_exported(wq):
+    """Hidden visibility: the dynamic symbol table holds the wq_* entry points and nothing else of
+    the library's own (no mangled launchers)."""
+    import subprocess
+    out = subprocess.run(["nm", "-D", "--defined-only", wq.LIB_PATH], capture_output=True, text=True, check=True).stdout
+    names = [l.split()[-1] for l in out.splitlines() if l.strip()]
+    own = [n for n in names if "wq" in n.lower()]
+    assert sorted(own) == sorted(wq.EXPORTS), sorted(set(own) ^ set(wq.EXPORTS))
+    assert not [n for n in names if n.startswith("_Z") and "wq_" in n]
+
+
+def test_plan_tune_is_validated_on_the_host(wq):
+    p = wq.Plan(2, 64, 64, 640, 320, 4, 64)
+    auto = p.layout.k2_variant
+    assert p.layout.k2_kernels in (1, 2) and p.layout.k1_rows in (1, 2, 3, 6)
+    for name, code in wq.K2_VARIANTS.items():
+        if name in ("auto", "gemm_128x128"):
+            continue
+        p.tune(0, name)
+        assert p.layout.k2_variant == code
+        assert p.layout.k2_kernels == (2 if name.startswith(("gemm", "lds_row")) else 1)
+    with pytest.raises(wq.WqError) as e:
+        p.tune(0, "gemm_128x128")        # groups of 64: that instance needs 128 and more
+    assert e.value.status == 2
+    assert p.layout.k2_variant == wq.K2_VARIANTS["lds_row_32x64"]      # unchanged by the failed call
+    with pytest.raises(wq.WqError) as e:
+        p.tune(0, 7)                     # not a variant
+    assert e.value.status == 1
+    with pytest.raises(wq.WqError) as e:
+        p.tune(5, "auto")                # 5 tap rows do not divide n = 6
+    assert e.value.status == 2
+    p.tune(0, "auto")
+    assert p.layout.k2_variant == auto
+    p.tune(3)
+    assert p.layout.k1_rows == 3
+    # F(6,3) has no 64x64 fully fused instance; F(2,3) and dense A^T none of the register-tile ones
+    with pytest.raises(wq.WqError):
+        wq.Plan(1, 12, 12, 64, 64, 6, 32).tune(0, "lds_full_64x64")
+    with pytest.raises(wq.WqError):
+        wq.Plan(1, 12, 12, 64, 64, 2, 32).tune(0, "fused_32x32")
+    assert wq.lib().wq_plan_tune(None, 0, -1) == 1
+    # the standard-convolution plan's split override
+    d = wq.DirectPlan(1, 8, 8, 64, 64, 32)
+    for s in (1, 3, 9):
+        assert d.tune(s).layout.splits == s
+    with pytest.raises(wq.WqError):
+        d.tune(2)
+    lin = wq.DirectPlan(8, 1, 1, 256, 64, 32, linear=True)
+    assert lin.tune(4).layout.splits == 4
+    with pytest.raises(wq.WqError):
+        lin.tune(3)
 
 
 def test_layout_numbers(wq):

@@ -29,10 +29,14 @@ def matrices_for(d, wq):
     return None
 
 
-def run_gpu(wq, d, mats, want_P=True):
+def run_gpu(wq, d, mats, want_P=True, variant=None, k1_rows=0):
     lay = d.layer
     kw = {} if mats is None else dict(AT=mats[0], BT=mats[1], G=mats[2])
     plan = wq.Plan(lay.N, lay.H, lay.W, lay.Cin, lay.Cout, lay.m, lay.group_size, **kw)
+    if variant is not None or k1_rows:
+        plan.tune(k1_rows, "auto" if variant is None else variant)
+        if variant is not None:
+            assert plan.k2_variant_name == variant
     L = plan.layout
     blob, ws, y = plan.alloc_blob(), plan.alloc_workspace(), plan.alloc_output()
     y.fill_(float("nan"))
@@ -40,8 +44,8 @@ def run_gpu(wq, d, mats, want_P=True):
     w = torch.from_numpy(d.w).cuda()
     b = torch.from_numpy(d.bias).cuda() if d.bias is not None else None
     plan.weight_prepare(w, b, blob)
-    # the production entry point picks its own tile configuration; the debug
-    # entry point (int32 dump) always runs the basic one - check both outputs
+    # the debug entry point launches the same kernel instances as the production one (the dump
+    # sits behind a run-time flag inside them); both outputs are checked
     plan.forward(x, blob, ws, y)
     torch.cuda.synchronize()
     P, y_dbg = None, None
@@ -62,14 +66,17 @@ def run_gpu(wq, d, mats, want_P=True):
     out = dict(M=plan.product_view(ws).cpu().numpy(), y_split=y_split.cpu().numpy(),Wq=Wq[:, :L.Cout].cpu().numpy(), sW=sW[:, :, :L.Cout].cpu().numpy(),
                Xq=Xq[:, :L.T].cpu().numpy(), sX=sX[:, :L.T].cpu().numpy(),
                y=y.cpu().numpy(), P=None if P is None else P.cpu().numpy(),
-               y_dbg=None if y_dbg is None else y_dbg.cpu().numpy(),
+               y_dbg=None if y_dbg is None else y_dbg.cpu().numpy(), variant=plan.k2_variant_name,
                pad_ok=bool((Wq[:, L.Cout:] == 0).all() and (sW[:, :, L.Cout:] == 0).all()
                            and (Xq[:, L.T:] == 0).all() and (sX[:, L.T:] == 0).all()
                            and (bias[L.Cout:] == 0).all()))
     return out
 
 
-def check(wq, d, want_P=True):
+SEEN_VARIANTS = set()   # kernel instances of stages 2+3 whose int32 sums were compared so far
+
+
+def check(wq, d, want_P=True, variant=None, k1_rows=0):
     lay = d.layer
     mats = matrices_for(d, wq)
     if mats is None:
@@ -77,7 +84,7 @@ def check(wq, d, want_P=True):
     else:
         AT, BT, G = mats
     ref = oracle.qwino_pipeline(d.x, d.w, d.bias, AT, BT, G, lay.m, lay.group_size, want_P=want_P)
-    got = run_gpu(wq, d, mats, want_P=want_P)
+    got = run_gpu(wq, d, mats, want_P=want_P, variant=variant, k1_rows=k1_rows)
     assert got["pad_ok"]
     for key in ("Wq", "Xq"):
         bad = np.count_nonzero(got[key] != ref[key])
@@ -85,7 +92,8 @@ def check(wq, d, want_P=True):
     for key in ("sW", "sX"):
         assert np.array_equal(got[key].view(np.uint32), ref[key].view(np.uint32)), f"{lay.name}: {key}"
     if want_P:
-        assert np.array_equal(got["P"], ref["P"]), f"{lay.name}: int32 partial sums"
+        assert np.array_equal(got["P"], ref["P"]), f"{lay.name}: int32 partial sums ({got['variant']})"
+        SEEN_VARIANTS.add(got["variant"])
     scale = np.abs(ref["y64"]).max()
     worst = 0.0
     m_scale = np.abs(ref["M"]).max()
@@ -101,7 +109,7 @@ def check(wq, d, want_P=True):
         err = np.abs(got[key].astype(np.float64) - ref["y64"]).max()
         assert err <= Y_TOL * scale, f"{lay.name}: {key} max|err| {err:.3e} > {Y_TOL * scale:.3e}"
         worst = max(worst, err / max(scale, 1e-300))
-    print(f"{lay.name}: max|err|/max|y| = {worst:.2e}")
+    print(f"{lay.name} [{got['variant']}]: max|err|/max|y| = {worst:.2e}")
     return worst
 
 
@@ -181,11 +189,10 @@ FULL = [(c, i) for c in (2, 3, 4, 5) for i in range(len(workloads.CONFIGS[c]))]
 
 @pytest.mark.parametrize("cfg,idx", FULL, ids=lambda v: str(v))
 def test_config_layers_full_size(wq, cfg, idx):
+    """Every layer of configs 2-5 at full size, in the kernel instances the library picks for it
+    (the ones bench.py times), the whole int32 tensor P included (up to 472 MB)."""
     lay = workloads.CONFIGS[cfg][idx]
-    d = workloads.make_layer_data(lay)
-    n2 = lay.n ** 2
-    p_bytes = n2 * lay.tiles * (lay.Cin // lay.group_size) * lay.Cout * 4
-    check(wq, d, want_P=p_bytes <= 300 << 20)
+    check(wq, workloads.make_layer_data(lay))
 
 
 def test_graph_replay_matches_eager(wq):
@@ -231,9 +238,6 @@ def test_wide_layer_at_reduced_batch(wq, idx):
     import dataclasses
     d = workloads.make_layer_data(lay, N=4)
     d.layer = dataclasses.replace(lay, N=4)
-    import os
-    if "WQ_K2_PATH" not in os.environ:   # the library's own choice for a layer this wide
-        assert wq.Plan(4, lay.H, lay.W, lay.Cin, lay.Cout, lay.m, lay.group_size).layout.k2_kernels == 2
     check(wq, d, want_P=False)
 
 
@@ -270,13 +274,10 @@ def test_largest_supported_input(wq):
 
 
 def test_two_kernel_form_with_more_than_65535_tiles(wq):
-    """Groups of 128 take the GEMM + output-transform kernels; 100352 tiles is more than one
-    grid dimension other than x holds."""
+    """The GEMM + output-transform kernels with 100352 tiles, more than a grid dimension other
+    than x holds."""
     d = workloads.small_layer(79, 32, 112, 112, 128, 32, 2, 128)
-    import os
-    if "WQ_K2_PATH" not in os.environ:
-        assert wq.Plan(32, 112, 112, 128, 32, 2, 128).layout.k2_kernels == 2
-    check(wq, d, want_P=False)
+    check(wq, d, want_P=False, variant="gemm_64x64")
 
 
 def test_two_plans_on_two_streams_at_once(wq):
@@ -303,3 +304,82 @@ def test_two_plans_on_two_streams_at_once(wq):
         torch.cuda.synchronize()
         for c in ctx:
             assert torch.equal(c["y"], c["want"]), f"repetition {rep}"
+
+
+# ---- every kernel instance of stages 2+3, forced through wq_plan_tune ----
+VARIANT_SHAPES = [
+    # seed N  H   W  Cin Cout m  g   scaled
+    (201, 2, 20, 20, 128, 96, 4, 64, False),    # 50 tiles -> 64 padded, Cout padded
+    (202, 1, 37, 23, 64, 80, 4, 32, True),      # ragged both ways, groups of 32 (K-step 32)
+    (203, 2, 30, 30, 64, 64, 6, 32, False),     # F(6,3)
+    (204, 1, 16, 16, 512, 40, 4, 128, False),   # several K-steps per group
+    (205, 3, 10, 10, 640, 48, 4, 64, True),     # more than 8 groups: fp64 chunk totals
+    (206, 2, 12, 12, 64, 32, 2, 32, False),     # F(2,3)
+    (207, 1, 24, 24, 768, 70, 6, 32, True),     # F(6,3), 24 groups, odd channel count
+]
+ALL_VARIANTS = ["fused_16x16", "fused_ksplit", "fused_32x16", "fused_32x32", "gemm_64x64", "gemm_32x128",
+                "gemm_128x128", "lds_full_64x64", "lds_full_32x64", "lds_row_64x64", "lds_row_32x64"]
+
+
+@pytest.mark.parametrize("variant", ALL_VARIANTS)
+def test_every_k2_variant(wq, variant):
+    """Each kernel instance on every shape it applies to: int8 codes, scales and the int32 sums
+    dumped by THAT instance bit-exact, outputs within the bound."""
+    ran = 0
+    for case in VARIANT_SHAPES:
+        seed, N, H, W, Cin, Cout, m, g, scaled = case
+        d = workloads.small_layer(seed, N, H, W, Cin, Cout, m, g, row_scales=scaled)
+        try:
+            check(wq, d, variant=variant)
+            ran += 1
+        except wq.WqError as e:
+            assert e.status == 2, e      # WQ_ERR_UNSUPPORTED: the variant does not apply to this shape
+    assert ran >= 1, f"{variant} applied to none of the shapes"
+    assert variant in SEEN_VARIANTS
+
+
+@pytest.mark.parametrize("rows", [1, 2, 3, 6])
+def test_every_k1_row_split(wq, rows):
+    d = workloads.small_layer(211, 2, 21, 17, 96, 48, 4, 32)
+    check(wq, d, k1_rows=rows)
+
+
+def test_debug_slab_equals_the_full_dump(wq):
+    d = workloads.small_layer(221, 2, 19, 14, 128, 72, 4, 64)
+    lay = d.layer
+    for variant in ("fused_32x16", "gemm_64x64", "lds_full_64x64", "lds_row_64x64"):
+        plan = wq.Plan(lay.N, lay.H, lay.W, lay.Cin, lay.Cout, lay.m, lay.group_size).tune(0, variant)
+        blob, ws, y = plan.alloc_blob(), plan.alloc_workspace(), plan.alloc_output()
+        x = torch.from_numpy(d.x).cuda()
+        plan.weight_prepare(torch.from_numpy(d.w).cuda(), torch.from_numpy(d.bias).cuda(), blob)
+        P = plan.alloc_debug_P()
+        plan.forward_debug(x, blob, ws, y, P)
+        full = P.cpu().numpy()
+        L = plan.layout
+        for tap0, ntaps, tile0, ntiles in ((0, 1, 0, 1), (5, 7, 13, 20), (35, 1, L.T - 1, 1), (0, 36, 0, L.T)):
+            slab = plan.forward_debug_slab(x, blob, ws, y, tap0, ntaps, tile0, ntiles).cpu().numpy()
+            assert np.array_equal(slab, full[tap0:tap0 + ntaps, tile0:tile0 + ntiles]), (variant, tap0, tile0)
+        with pytest.raises(wq.WqError):
+            plan.forward_debug_slab(x, blob, ws, y, 30, 7, 0, 1)          # taps past the end
+        with pytest.raises(wq.WqError):
+            plan.forward_debug_slab(x, blob, ws, y, 0, 1, L.T, 1)         # tiles past the end
+
+
+def test_adversarially_rounded_column_scales_take_the_dense_output_transform(wq):
+    """A^T whose paired columns agree only to several ulps (entries nudged after the scaling):
+    the library must use every entry as given, like the oracle does."""
+    d = workloads.small_layer(231, 1, 13, 13, 64, 32, 6, 32, row_scales=True)
+    lay = d.layer
+    AT, BT, G = (M.astype(np.float32) for M in ct.scaled_matrices(lay.m, d.u_B, d.u_G))
+    AT = AT.copy()
+    bits = AT.view(np.uint32)
+    nudge = np.zeros(AT.shape, np.uint32)
+    nudge[1::2, 2::2] = 3          # three ulps on every other entry of the even columns
+    nudge[0::2, 1::2] = 2
+    bits += nudge * (AT != 0)      # the exact zeros of the first and last columns stay
+    ref = oracle.qwino_pipeline(d.x, d.w, d.bias, AT, BT, G, lay.m, lay.group_size, want_P=False)
+    got = run_gpu(wq, d, (AT, BT, G), want_P=False)
+    scale = np.abs(ref["y64"]).max()
+    for key in ("y", "y_split"):
+        err = np.abs(got[key].astype(np.float64) - ref["y64"]).max()
+        assert err <= Y_TOL * scale, (key, err / scale)

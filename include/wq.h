@@ -200,6 +200,23 @@ wq_status_t wq_conv_forward(const wq_plan_t *plan, void *stream, const float *x_
                             const void *weight_blob_dev, size_t blob_bytes,
                             void *workspace_dev, size_t workspace_bytes, float *y_dev);
 
+/* wq_conv_forward for callers that cannot allocate device memory or pass a
+ * workspace along: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  The workspace is a device array owned by
+ * the library, WQ_STATIC_WORKSPACE_BYTES large, one copy per GPU, held until the
+ * process ends; this call allocates nothing (its first call on a device looks
+ * up the array's address there).  A plan whose ws_bytes exceeds
+ * WQ_STATIC_WORKSPACE_BYTES -> WQ_ERR_WORKSPACE (checked on the host before any
+ * device call).  All calls on one GPU share the array: calls that overlap in
+ * time on the same GPU (two streams, two threads) race - serialise them or
+ * use wq_conv_forward with separate workspaces.  The array keeps the previous
+ * call's contents; nothing depends on them.  Inputs, weight blob and output
+ * are the caller's, as for wq_conv_forward, and the result is the same bit
+ * for bit. */
+#define WQ_STATIC_WORKSPACE_BYTES (32u << 20)
+wq_status_t wq_conv_forward_static(const wq_plan_t *plan, void *stream, const float *x_dev,
+                                   const void *weight_blob_dev, size_t blob_bytes, float *y_dev);
+
 /* wq_conv_forward with a dump of the exact int32 group partial sums
  * P[t][tile][group][o] = sum_{c in group} Xq[t][tile][c] * Wq[t][o][c] (the
  * integer product inside the second quantized-stage equation of Section

@@ -20,7 +20,7 @@ LIB = os.path.join(HERE, "libwq.so")
 SOURCES = ["wq_host.cpp", "wq_transform.hip", "wq_contract.hip", "wq_contract_m2.hip",
            "wq_contract_m4.hip", "wq_contract_m6.hip", "wq_contract_lds.hip", "wq_contract_lds_m4.hip", "wq_contract_lds_m4_dump.hip",
            "wq_contract_lds_m6.hip", "wq_contract_lds_m6_dump.hip", "wq_gemm_unfused.hip",
-           "wq_direct.hip", "wq_microbench.hip"]
+           "wq_direct.hip", "wq_microbench.hip", "wq_static.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-ffp-contract=off",
          "-fvisibility=hidden",   # only the extern "C" entry points of include/wq.h are exported

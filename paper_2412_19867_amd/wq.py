@@ -15,13 +15,14 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libwq.so")
 
 WQ_OK = 0
+STATIC_WORKSPACE_BYTES = 32 << 20   # WQ_STATIC_WORKSPACE_BYTES of include/wq.h
 STATUS_NAMES = {0: "WQ_OK", 1: "WQ_ERR_INVALID_ARG", 2: "WQ_ERR_UNSUPPORTED",
                 3: "WQ_ERR_BAD_TRANSFORM", 4: "WQ_ERR_NOT_PREPARED", 5: "WQ_ERR_WORKSPACE",
                 6: "WQ_ERR_DEVICE"}
 
 EXPORTS = ["wq_standard_transforms", "wq_scaled_transforms", "wq_plan_create", "wq_plan_destroy",
            "wq_plan_layout", "wq_plan_tune", "wq_conv_forward_debug_slab", "wq_direct_plan_tune",
-           "wq_contract_output_part", "wq_microbench_dequant",
+           "wq_contract_output_part", "wq_microbench_dequant", "wq_conv_forward_static",
            "wq_weight_prepare", "wq_input_transform", "wq_contract_output", "wq_contract",
            "wq_output_transform", "wq_conv_forward",
            "wq_direct_plan_create", "wq_linear_plan_create", "wq_direct_plan_create_bits",
@@ -90,6 +91,7 @@ def lib() -> ctypes.CDLL:
         L.wq_microbench_dequant.argtypes = [vp, ip, ip, ip, ip, ip, vp, vp, vp]
         L.wq_output_transform.argtypes = [vp, vp, vp, sz, vp, sz, vp]
         L.wq_conv_forward.argtypes = [vp, vp, vp, vp, sz, vp, sz, vp]
+        L.wq_conv_forward_static.argtypes = [vp, vp, vp, vp, sz, vp]
         L.wq_conv_forward_debug.argtypes = [vp, vp, vp, vp, sz, vp, sz, vp, vp, sz]
         L.wq_direct_plan_create.argtypes = [ctypes.POINTER(vp), ip, ip, ip, ip, ip, ip]
         L.wq_linear_plan_create.argtypes = [ctypes.POINTER(vp), ip, ip, ip, ip]
@@ -318,6 +320,16 @@ class Plan:
                                      _dev_ptr(ws, torch.uint8, "workspace"), ws.numel(),
                                      _dev_ptr(y, torch.float32, "y", L.N * L.H * L.W * L.Cout)),
                "wq_conv_forward")
+
+    def forward_static(self, x, blob, y, stream=None):
+        """wq_conv_forward_static: the library's own static workspace, nothing allocated."""
+        import torch
+        L = self.layout
+        _check(lib().wq_conv_forward_static(self._h, _stream_handle(stream),
+                                            _dev_ptr(x, torch.float32, "x", L.N * L.H * L.W * L.Cin),
+                                            _dev_ptr(blob, torch.uint8, "blob"), blob.numel(),
+                                            _dev_ptr(y, torch.float32, "y", L.N * L.H * L.W * L.Cout)),
+               "wq_conv_forward_static")
 
     def forward_debug(self, x, blob, ws, y, P, stream=None):
         import torch

@@ -2,23 +2,28 @@
 """Benchmark of the group-wise int8 quantized Winograd convolution on one MI355X.
 
 A step is one forward pass (input transform + quantization, int8 contraction
-with per-group dequantization, output transform + bias) over every layer of
-the workload, inputs and prepared weights resident in HBM.  The step's kernel
-launches are captured once into a HIP graph (the layers are a few microseconds
-each, so host launch cost would otherwise dominate) and the timed region
-replays that graph.  The weight transform is the method's offline stage: it
-runs once before the timed region and is timed separately (per layer in
-"layers", and as a second whole-job figure "with_offline_stage" that re-runs
-it inside every step).
+with per-group dequantization, output transform + bias) over every convolution
+of the workload, inputs and prepared weights resident in HBM, all launches on
+one stream.  The headline workload is the largest single-GPU configuration:
+configs[4], the SDXL-scale stack (12 chained 3x3 convolutions at 128x128, 64x64
+and 32x32 latent resolution, F(4,3), groups of 64).  The K timed steps are
+launched in three ways (one HIP graph replay per step, one replay of a graph
+holding several steps, plain launches); every way is timed REPEATS times and
+its median taken, and the fastest way's median is the reported figure.  The
+weight transform is the method's offline stage: it runs once before the timed
+region and is timed separately ("with_offline_stage" re-runs it inside every
+step).
 
-Prints ONE JSON line.  `value` = direct-equivalent int8 TOPS of the layer set
-(2*N*H*W*Cin*Cout*9 per layer / measured time).
+Prints ONE JSON line.  `value` = direct-equivalent int8 TOPS of the workload
+(2*N*H*W*Cin*Cout*9 per convolution / measured time).
 """
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import os
+import statistics
 import sys
 import time
 
@@ -28,7 +33,8 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 INT8_PEAK_TOPS = 5000.0        # MI355X published dense int8 MFMA rate
-VALU_PEAK_OPS = 256 * 64 * 2.4e9   # fp32 vector operations per second without packed math: 256 CUs x 4 SIMDs x 16 lanes
+VALU_PEAK_OPS = 78.65e12       # fp32 vector operations per second: the published 157.3 TFLOP/s counts a multiply-add as two
+REPEATS = 10                   # timed repetitions of the --steps block per launch mode (median reported)
 
 
 def k1_bytes(lay):
@@ -47,28 +53,54 @@ def k3_bytes(lay):
     return 36 * lay.Cin * lay.Cout + n2 * lay.Cout * (lay.Cin + 4 * G)
 
 
+def k2_ceilings_us(lay):
+    """The three lower bounds of stages 2+3 in microseconds: algorithmic bytes at the HBM peak, the
+    Winograd-domain int8 multiply-adds at the MFMA peak, and the plain vector-ALU work the method
+    forces (3 fp32 operations per output element, tap and group for the dequantization)."""
+    n2, G = lay.n ** 2, lay.Cin // lay.group_size
+    return dict(hbm=k2_bytes(lay) / (HBM_PEAK_GBS * 1e9) * 1e6,
+                mfma=2 * n2 * lay.tiles * lay.Cin * lay.Cout / (INT8_PEAK_TOPS * 1e12) * 1e6,
+                valu=3 * n2 * lay.tiles * G * lay.Cout / VALU_PEAK_OPS * 1e6)
+
+
+def library_sources_sha256():
+    """Hash of the kernel sources the library is built from: a counter summary under profiles/
+    names the hash it was measured with, and is ignored when the sources have changed since."""
+    h = hashlib.sha256()
+    d = os.path.join(ROOT, "paper_2412_19867_amd", "csrc")
+    for name in sorted(os.listdir(d)):
+        if name.endswith((".hip", ".h", ".cpp")):
+            h.update(name.encode())
+            h.update(open(os.path.join(d, name), "rb").read())
+    return h.hexdigest()[:16]
+
+
 def measured_traffic(kernel, cfg):
-    """HBM bytes per step of the dominant kernel as measured with rocprofv3 --pmc
-    (FETCH_SIZE + WRITE_SIZE, calibrated against a copy kernel); read from the
-    committed summary, None when there is none for this kernel and layer set."""
+    """HBM bytes per step of a kernel from rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, calibrated
+    against a copy kernel), read from the committed summary profiles/<kernel>_cfg<N>_hbm_traffic.txt.
+    Returns (bytes or None, note)."""
     path = os.path.join(ROOT, "profiles", f"{kernel}_cfg{cfg}_hbm_traffic.txt")
     try:
-        for line in open(path):
-            if line.startswith("traffic_bytes_per_step:"):
-                return int(float(line.split(":")[1]))
+        fields = dict(line.split(":", 1) for line in open(path) if ":" in line and not line.startswith("#"))
     except OSError:
-        pass
-    return None
+        return None, "no counter summary for this kernel and workload under profiles/"
+    sha = fields.get("library_sources_sha256", "").strip()
+    if sha != library_sources_sha256():
+        return None, f"profiles/{os.path.basename(path)} was measured with other kernel sources ({sha}): ignored"
+    return int(float(fields["traffic_bytes_per_step"])), f"profiles/{os.path.basename(path)}"
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", type=int, default=2, help="layer set 1..5 (2 = the headline one); 6 = an extra large GEMM-shaped layer at "
-                         "two group sizes, outside the five configurations (no host baseline)")
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=5,
+                    help="layer set 1..5 (5 = the headline one, configs[4]); 6 = an extra large GEMM-shaped "
+                         "layer at two group sizes, outside the five configurations (no host baseline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the comparison layer, the linear layer and the other configurations")
     ap.add_argument("--eager", action="store_true",
                     help="launch the step from Python instead of replaying a HIP graph (for profilers)")
     ap.add_argument("--only-steps", action="store_true",
@@ -97,43 +129,30 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"copy_bytes_read": src.numel() * 4, "copy_bytes_written": src.numel() * 4}))
         return
-    stream = torch.cuda.current_stream()
-
-    layers = workloads.CONFIGS[args.config]
-    items = []      # one entry per conv launched in a step (a layer with repeat=r gives r chained convs)
-    for lay in layers:
-        d = workloads.make_layer_data(lay)
-        kw = {}
-        if d.u_B is not None:
-            AT, BT, G = wq.scaled_transforms(lay.m, d.u_B, d.u_G)
-            kw = dict(AT=AT, BT=BT, G=G)
-        plan = wq.Plan(lay.N, lay.H, lay.W, lay.Cin, lay.Cout, lay.m, lay.group_size, **kw)
-        x = torch.from_numpy(d.x).cuda()
-        w, b = torch.from_numpy(d.w).cuda(), torch.from_numpy(d.bias).cuda()
-        for r in range(lay.repeat):
-            # conv r of a stack reads conv r-1's output (Cin == Cout) and has its own weight blob
-            it = dict(lay=lay, plan=plan, x=x, w=w, b=b, blob=plan.alloc_blob(),
-                      ws=plan.alloc_workspace(), y=plan.alloc_output(), data=d, first=(r == 0))
-            plan.weight_prepare(w, b, it["blob"])
-            items.append(it)
-            x = it["y"]
-    torch.cuda.synchronize()
-
-    def step(with_offline=False):
-        for it in items:
-            if with_offline:
-                it["plan"].weight_prepare(it["w"], it["b"], it["blob"])
-            it["plan"].forward(it["x"], it["blob"], it["ws"], it["y"])
-
-    if args.only_steps:
-        for _ in range(args.warmup + args.steps):
-            step()
-        torch.cuda.synchronize()
-        print(json.dumps({"steps_launched": args.warmup + args.steps, "convs_per_step": len(items),
-                          "offline_stage_launches": len(items)}))
-        return
 
     side = torch.cuda.Stream()
+
+    def build_items(cfg):
+        """One entry per convolution launched in a step (a layer with repeat=r gives r chained convs)."""
+        items = []
+        for lay in workloads.CONFIGS[cfg]:
+            d = workloads.make_layer_data(lay)
+            kw = {}
+            if d.u_B is not None:
+                AT, BT, G = wq.scaled_transforms(lay.m, d.u_B, d.u_G)
+                kw = dict(AT=AT, BT=BT, G=G)
+            plan = wq.Plan(lay.N, lay.H, lay.W, lay.Cin, lay.Cout, lay.m, lay.group_size, **kw)
+            x = torch.from_numpy(d.x).cuda()
+            w, b = torch.from_numpy(d.w).cuda(), torch.from_numpy(d.bias).cuda()
+            for r in range(lay.repeat):
+                # conv r of a stack reads conv r-1's output (Cin == Cout) and has its own weight blob
+                it = dict(lay=lay, plan=plan, x=x, w=w, b=b, blob=plan.alloc_blob(),
+                          ws=plan.alloc_workspace(), y=plan.alloc_output(), data=d, first=(r == 0))
+                plan.weight_prepare(w, b, it["blob"])
+                items.append(it)
+                x = it["y"]
+        torch.cuda.synchronize()
+        return items
 
     def capture(fn):
         """Record fn's launches on a side stream into a HIP graph."""
@@ -146,42 +165,60 @@ def main():
         torch.cuda.synchronize()
         return g
 
-    def timed_replays(g, steps, warmup):
+    def timed(run_once, calls, warmup_calls, repeats=REPEATS):
+        """Median over `repeats` of (wall time of `calls` back-to-back calls) / calls, each repetition
+        bracketed by synchronisations."""
         with torch.cuda.stream(side):
-            for _ in range(warmup):
-                g.replay()
+            for _ in range(warmup_calls):
+                run_once()
             torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            for _ in range(steps):
-                g.replay()
-            torch.cuda.synchronize()
-            return (time.perf_counter() - t0) / steps
+            samples = []
+            for _ in range(repeats):
+                t0 = time.perf_counter()
+                for _ in range(calls):
+                    run_once()
+                torch.cuda.synchronize()
+                samples.append((time.perf_counter() - t0) / calls)
+        return statistics.median(samples), samples
 
-    # Three ways to launch the same K steps; the timed figure is the fastest one, named in
-    # "launch".  (a) one graph per step, replayed K times; (b) one graph holding 10 steps,
-    # replayed K/10 times (a replay costs several microseconds of its own, which a 120 us
-    # step notices); (c) plain launches from Python, which run asynchronously ahead of the GPU.
-    def timed_eager(steps, warmup):
-        for _ in range(warmup):
+    def time_step(step, steps, warmup, eager_only=False):
+        """The three launch modes of K steps; returns {mode: median seconds per step} and the spreads."""
+        timings, spread = {}, {}
+
+        def put(name, med_samples, per_call=1):
+            med, samples = med_samples
+            timings[name] = med / per_call
+            spread[name] = [round(min(samples) / per_call * 1e3, 4), round(max(samples) / per_call * 1e3, 4)]
+
+        if not eager_only:
+            g_step = capture(step)
+            put("one HIP graph replay per step", timed(g_step.replay, steps, warmup))
+            group = 10 if steps % 10 == 0 else (5 if steps % 5 == 0 else 1)
+            if group > 1:
+                gN = capture(lambda: [step() for _ in range(group)])
+                put(f"HIP graph of {group} steps, replayed steps/{group} times",
+                    timed(gN.replay, steps // group, max(1, warmup // group)), group)
+        put("eager launches from Python", timed(step, steps, warmup))
+        return timings, spread
+
+    items = build_items(args.config)
+    layers = workloads.CONFIGS[args.config]
+
+    def step(with_offline=False):
+        for it in items:
+            if with_offline:
+                it["plan"].weight_prepare(it["w"], it["b"], it["blob"])
+            it["plan"].forward(it["x"], it["blob"], it["ws"], it["y"])
+
+    if args.only_steps:
+        for _ in range(args.warmup + args.steps):
             step()
         torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(steps):
-            step()
-        torch.cuda.synchronize()
-        return (time.perf_counter() - t0) / steps
+        print(json.dumps({"steps_launched": args.warmup + args.steps, "convs_per_step": len(items),
+                          "kernels": sorted({it["plan"].k2_variant_name for it in items})}))
+        return
 
-    timings = {}
-    if args.eager:
-        timings["eager launches from Python"] = timed_eager(args.steps, args.warmup)
-    else:
-        g_step = capture(step)
-        timings["one HIP graph replay per step"] = timed_replays(g_step, args.steps, args.warmup)
-        if args.steps % 10 == 0:
-            g10 = capture(lambda: [step() for _ in range(10)])
-            timings["HIP graph of 10 steps, replayed steps/10 times"] = \
-                timed_replays(g10, args.steps // 10, max(1, args.warmup // 10)) / 10
-        timings["eager launches from Python"] = timed_eager(args.steps, args.warmup)
+    timings, spread = time_step(step, args.steps, args.warmup, eager_only=args.eager)
     launch_mode = min(timings, key=timings.get)
     sec = timings[launch_mode]
     n_convs = len(items)
@@ -189,186 +226,175 @@ def main():
     value = direct_ops / sec / 1e12
 
     g_off = capture(lambda: step(True))
-    sec_off = timed_replays(g_off, max(10, args.steps // 4), 3)
-
-    # ---- the same step with cold caches: consecutive steps use different copies of every buffer
-    # (inputs, weight blobs, workspaces, outputs), enough copies to exceed the 256 MB Infinity Cache
-    # twice over, so nothing a step reads is left over from the step before.  Reported beside the
-    # warm figure, which is the timed one: inside a network the activations a layer reads were
-    # written just before and are warm, its weights are not.
+    sec_off, _ = timed(g_off.replay, max(5, args.steps // 4), 2, repeats=5)
     footprint = sum(it["x"].numel() * 4 * it["first"] + it["blob"].numel() + it["ws"].numel()
                     + it["y"].numel() * 4 for it in items)
-    cold = None
-    n_sets = min(8, -(-(512 << 20) // footprint)) if footprint < (512 << 20) else 1
-    if n_sets > 1:
-        sets = [items]
-        for _ in range(n_sets - 1):
-            clone, x_prev = [], None
-            for it in items:
-                c = dict(it)
-                c["x"] = it["x"].clone() if it["first"] else x_prev
-                c["blob"], c["ws"], c["y"] = it["blob"].clone(), torch.empty_like(it["ws"]), torch.empty_like(it["y"])
-                x_prev = c["y"]
-                clone.append(c)
-            sets.append(clone)
 
-        def step_of(k):
-            for it in sets[k % n_sets]:
-                it["plan"].forward(it["x"], it["blob"], it["ws"], it["y"])
-
-        for k in range(n_sets * 2):
-            step_of(k)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for k in range(args.steps):
-            step_of(k)
-        torch.cuda.synchronize()
-        sec_cold = (time.perf_counter() - t0) / args.steps
-        cold = dict(buffer_sets=n_sets, footprint_mb_per_set=round(footprint / 1e6, 1),
-                    ms_per_step=round(sec_cold * 1e3, 4), value=round(direct_ops / sec_cold / 1e12, 2),
-                    unit="TOPS", launch="eager launches from Python")
-        del sets
-
-    # ---- per-kernel durations: HIP events on the replay stream around a graph that
-    # launches ONE kernel REPS times back to back (so the figure is device time, not
-    # host launch cost) ----
+    # ---- per-kernel durations: HIP events on the replay stream around a graph that launches ONE
+    # kernel REPS times back to back (device time, not host launch cost); median of 5 replays ----
     REPS = 20
 
     def kernel_us(fn):
         g = capture(lambda: [fn() for _ in range(REPS)])
+        samples = []
         with torch.cuda.stream(side):
             g.replay()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record(side)
             for _ in range(5):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(side)
                 g.replay()
-            e1.record(side)
-            torch.cuda.synchronize()
-        return e0.elapsed_time(e1) * 1e3 / (5 * REPS)
+                e1.record(side)
+                torch.cuda.synchronize()
+                samples.append(e0.elapsed_time(e1) * 1e3 / REPS)
+        return statistics.median(samples)
 
-    k1_us = [kernel_us(lambda it=it: it["plan"].input_transform(it["x"], it["ws"])) for it in items]
-    k2_us = [kernel_us(lambda it=it: it["plan"].contract_output(it["ws"], it["blob"], it["y"]))
-             for it in items]
-    k3_us = [kernel_us(lambda it=it: it["plan"].weight_prepare(it["w"], it["b"], it["blob"]))
-             for it in items]
-    # layers whose stages 2+3 run as two kernels: each kernel on its own
-    split_us = {k: (kernel_us(lambda it=it: it["plan"].contract(it["ws"], it["blob"])),
-                    kernel_us(lambda it=it: it["plan"].output_transform(it["ws"], it["blob"], it["y"])))
-                for k, it in enumerate(items) if it["plan"].layout.k2_kernels == 2}
+    # identical convolutions of a stack (same plan, same shapes) are timed once
+    cache = {}
 
-    per_layer = []
-    for k, it in enumerate(items):
-        lay = it["lay"]
-        t_us = k1_us[k] + k2_us[k]
-        per_layer.append(dict(
-            layer=lay.name, us=round(t_us, 2), k1_us=round(k1_us[k], 2), k2_us=round(k2_us[k], 2),
-            direct_equiv_tops=round(lay.direct_ops / t_us / 1e6, 1),
-            k1_hbm_frac=round(k1_bytes(lay) / (k1_us[k] * 1e-6) / 1e9 / HBM_PEAK_GBS, 3),
-            k2_hbm_frac=round(k2_bytes(lay) / (k2_us[k] * 1e-6) / 1e9 / HBM_PEAK_GBS, 3),
-            k2_mfma_frac=round(2 * lay.n ** 2 * lay.tiles * lay.Cin * lay.Cout
-                               / (k2_us[k] * 1e-6) / 1e12 / INT8_PEAK_TOPS, 4),
-            # the ceilings of stages 2+3: bytes, MFMA work, and the plain-ALU work the method
-            # forces (3 fp32 vector operations per output element, tap and group for the
-            # dequantization, unpacked: 256 CUs x 64 lanes x 2.4 GHz), each as time / measured time
-            k2_valu_frac=round(3 * lay.n ** 2 * lay.tiles * (lay.Cin // lay.group_size) * lay.Cout
-                               / (k2_us[k] * 1e-6) / VALU_PEAK_OPS, 4),
-            k2_kernels=it["plan"].layout.k2_kernels, k3_us=round(k3_us[k], 2),
-            k3_hbm_frac=round(k3_bytes(lay) / (k3_us[k] * 1e-6) / 1e9 / HBM_PEAK_GBS, 3)))
+    def per_plan(it, key, fn):
+        k = (id(it["plan"]), key)
+        if k not in cache:
+            cache[k] = kernel_us(fn)
+        return cache[k]
 
-    # per-kernel totals over one step.  Stages 2+3 of a layer are one fused kernel or,
-    # for layers with few tiles, a tiled GEMM followed by an output-transform kernel.
-    kernels = {}
+    FIRST_KERNEL = {"fused": "k_contract_output", "gemm": "k_gemm_dequant", "lds_full": "k_wino_lds_full",
+                    "lds_row": "k_wino_lds_row"}
+    SECOND_KERNEL = {"gemm": "k_output_transform", "lds_row": "k_row_finish"}
 
-    def account(name, us, nbytes, launches):
+    per_layer, kernels = [], {}
+
+    def account(name, us, nbytes):
         k = kernels.setdefault(name, dict(us=0.0, bytes=0, launches=0))
         k["us"] += us
         k["bytes"] += nbytes
-        k["launches"] += launches
+        k["launches"] += 1
 
-    for k, it in enumerate(items):
-        lay = it["lay"]
-        account("k_input_transform", k1_us[k], k1_bytes(lay), 1)
-        if it["plan"].layout.k2_kernels == 1:
-            account("k_contract_output", k2_us[k], k2_bytes(lay), 1)
+    for it in items:
+        lay, plan = it["lay"], it["plan"]
+        fam = plan.k2_variant_name.rsplit("_", 1)[0]
+        k1 = per_plan(it, "k1", lambda: plan.input_transform(it["x"], it["ws"]))
+        k2 = per_plan(it, "k2", lambda: plan.contract_output(it["ws"], it["blob"], it["y"]))
+        k3 = per_plan(it, "k3", lambda: plan.weight_prepare(it["w"], it["b"], it["blob"]))
+        ceil = k2_ceilings_us(lay)
+        k1_ceiling = k1_bytes(lay) / (HBM_PEAK_GBS * 1e9) * 1e6
+        k2_ceiling = max(ceil.values())
+        row = dict(layer=lay.name, us=round(k1 + k2, 2), k1_us=round(k1, 2), k2_us=round(k2, 2),
+                   direct_equiv_tops=round(lay.direct_ops / (k1 + k2) / 1e6, 1),
+                   k2_variant=plan.k2_variant_name, k2_kernels=plan.layout.k2_kernels,
+                   k1_hbm_frac=round(k1_ceiling / k1, 3),
+                   k2_hbm_frac=round(ceil["hbm"] / k2, 3), k2_mfma_frac=round(ceil["mfma"] / k2, 4),
+                   k2_valu_frac=round(ceil["valu"] / k2, 3),
+                   # the layer against its binding ceilings: stage 1 by bytes, stages 2+3 by the largest of
+                   # bytes, MFMA work and the dequantization's vector-ALU work
+                   ceiling_us=round(k1_ceiling + k2_ceiling, 2),
+                   ceiling_frac=round((k1_ceiling + k2_ceiling) / (k1 + k2), 3),
+                   k2_bound=max(ceil, key=ceil.get),
+                   k3_us=round(k3, 2), k3_hbm_frac=round(k3_bytes(lay) / (k3 * 1e-6) / 1e9 / HBM_PEAK_GBS, 3))
+        account("k_input_transform", k1, k1_bytes(lay))
+        if plan.layout.k2_kernels == 1:
+            account(FIRST_KERNEL[fam], k2, k2_bytes(lay))
         else:
-            # the fp32 product tensor M is written by the GEMM and read back by the transform
-            m_bytes = 4 * lay.n ** 2 * lay.tiles * lay.Cout
+            a_us = per_plan(it, "k2a", lambda: plan.contract_output_part(it["ws"], it["blob"], it["y"], 1))
+            b_us = per_plan(it, "k2b", lambda: plan.contract_output_part(it["ws"], it["blob"], it["y"], 2))
+            # the fp32 intermediate (the n*n Winograd-domain products, or the n*m row sums of the row
+            # form) is written by the first kernel and read back by the second
+            per_elem = lay.n ** 2 if fam == "gemm" else lay.n * lay.m
+            mid_bytes = 4 * per_elem * lay.tiles * lay.Cout
             y_bytes = 4 * lay.N * lay.H * lay.W * lay.Cout
-            account("k_gemm_dequant", split_us[k][0], k2_bytes(lay) - y_bytes + m_bytes, 1)
-            account("k_output_transform", split_us[k][1], m_bytes + y_bytes, 1)
+            account(FIRST_KERNEL[fam], a_us, k2_bytes(lay) - y_bytes + mid_bytes)
+            account(SECOND_KERNEL[fam], b_us, mid_bytes + y_bytes)
+            row.update(k2_first_us=round(a_us, 2), k2_second_us=round(b_us, 2))
+        per_layer.append(row)
+
     dom = max(kernels, key=lambda name: kernels[name]["us"])
     dk = kernels[dom]
     achieved = dk["bytes"] / (dk["us"] * 1e-6) / 1e9
+    traffic, traffic_note = measured_traffic(dom, args.config)
     roofline = dict(bound="hbm", kernel=dom, achieved=round(achieved, 1), peak=HBM_PEAK_GBS,
                     unit="GB/s", frac=round(achieved / HBM_PEAK_GBS, 4),
-                    traffic=measured_traffic(dom, args.config),
+                    traffic=traffic, traffic_source=traffic_note,
                     algorithmic_bytes_per_step=dk["bytes"],
                     avg_launch_us=round(dk["us"] / dk["launches"], 2),
                     launches_per_step=dk["launches"],
+                    note="every configured layer is bound by bytes when its kernels are priced one by one "
+                         "(algorithmic bytes / HBM peak exceeds MFMA time and, except where 'k2_bound' says "
+                         "otherwise, the dequantization's vector-ALU time); 'layers[].ceiling_frac' prices "
+                         "each layer against the largest of the three",
                     kernels={name: dict(us_per_step=round(v["us"], 2), launches=v["launches"],
                                         algorithmic_bytes=v["bytes"],
                                         hbm_frac=round(v["bytes"] / (v["us"] * 1e-6) / 1e9 / HBM_PEAK_GBS, 4))
                              for name, v in kernels.items()})
+    sum_ceiling = sum(r["ceiling_us"] for r in per_layer)
+    ceiling = dict(step_ceiling_us=round(sum_ceiling, 1), step_us=round(sec * 1e6, 1),
+                   frac=round(sum_ceiling / (sec * 1e6), 3))
 
-    # ---- the paper's runtime comparison point on the same layers: the group-wise quantized
-    # standard (direct) convolution, same quantizer and groups, no transforms
-    d_items = []
-    for it in items:
-        lay = it["lay"]
-        dp = wq.DirectPlan(lay.N, lay.H, lay.W, lay.Cin, lay.Cout, lay.group_size)
-        dit = dict(plan=dp, blob=dp.alloc_blob(), ws=dp.alloc_workspace(), x=it["x"], y=it["y"])
-        dp.weight_prepare(it["w"], it["b"], dit["blob"])
-        d_items.append(dit)
-    torch.cuda.synchronize()
+    direct = linear = others = None
+    if not args.no_extras:
+        # ---- the paper's runtime comparison point on the same layers: the group-wise quantized
+        # standard (direct) convolution, same quantizer and groups, no transforms
+        d_items = []
+        for it in items:
+            lay = it["lay"]
+            dp = wq.DirectPlan(lay.N, lay.H, lay.W, lay.Cin, lay.Cout, lay.group_size)
+            dit = dict(plan=dp, blob=dp.alloc_blob(), ws=dp.alloc_workspace(), x=it["x"], y=it["y"])
+            dp.weight_prepare(it["w"], it["b"], dit["blob"])
+            d_items.append(dit)
+        torch.cuda.synchronize()
 
-    def direct_step():
-        for dit in d_items:
-            dit["plan"].forward(dit["x"], dit["blob"], dit["ws"], dit["y"])
+        def direct_step():
+            for dit in d_items:
+                dit["plan"].forward(dit["x"], dit["blob"], dit["ws"], dit["y"])
 
-    # same launch choices as for the Winograd step (graph per step / graph of 10 steps)
-    sec_direct = timed_replays(capture(direct_step), max(10, args.steps // 2), 5)
-    if args.steps % 10 == 0:
-        g10d = capture(lambda: [direct_step() for _ in range(10)])
-        sec_direct = min(sec_direct, timed_replays(g10d, max(2, args.steps // 20), 1) / 10)
-    dq_us = [kernel_us(lambda dit=dit: dit["plan"].quantize(dit["x"], dit["ws"])) for dit in d_items]
-    dc_us = [kernel_us(lambda dit=dit: dit["plan"].conv(dit["ws"], dit["blob"], dit["y"])) for dit in d_items]
-    direct = dict(value=round(direct_ops / sec_direct / 1e12, 2), unit="TOPS",
-                  ms_per_step=round(sec_direct * 1e3, 4),
-                  winograd_over_direct=round(sec_direct / sec, 3),
-                  layers=[dict(layer=it["lay"].name, quantize_us=round(dq_us[k], 2),
-                               conv_us=round(dc_us[k], 2)) for k, it in enumerate(items)])
-    # the step above overwrote y with the direct path's outputs; restore the Winograd results
-    step()
-    torch.cuda.synchronize()
+        d_timings, _ = time_step(direct_step, max(5, args.steps // 2), 2)
+        sec_direct = min(d_timings.values())
+        direct = dict(value=round(direct_ops / sec_direct / 1e12, 2), unit="TOPS",
+                      ms_per_step=round(sec_direct * 1e3, 4),
+                      winograd_over_direct=round(sec_direct / sec, 3),
+                      note="the paper reports 31.3 % less runtime for the Winograd layers on an Arm CPU: "
+                           "another machine and another layer mix")
+        del d_items
+        # the step above overwrote y with the direct path's outputs; restore the Winograd results
+        step()
+        torch.cuda.synchronize()
 
-    # ---- the same quantized GEMM core as a linear layer (one tap): one attention-sized projection
-    lin_R, lin_C, lin_g = 4096, 1280, 64
-    lp = wq.DirectPlan(lin_R, 1, 1, lin_C, lin_C, lin_g, linear=True)
-    lblob, lws, ly = lp.alloc_blob(), lp.alloc_workspace(), lp.alloc_output()
-    lx = torch.randn(lin_R, lin_C, device="cuda")
-    lp.weight_prepare(torch.randn(lin_C, lin_C, device="cuda") * 0.02, None, lblob)
-    lq_us = kernel_us(lambda: lp.quantize(lx, lws))
-    lc_us = kernel_us(lambda: lp.conv(lws, lblob, ly))
-    # the same layer with 4-bit weight codes (W4A8), and a decode-sized batch of 16 rows against a
-    # 5120 x 5120 weight matrix, where the weights are the traffic
-    lp4 = wq.DirectPlan(lin_R, 1, 1, lin_C, lin_C, lin_g, linear=True, weight_bits=4)
-    lblob4 = lp4.alloc_blob()
-    lp4.weight_prepare(torch.randn(lin_C, lin_C, device="cuda") * 0.02, None, lblob4)
-    lc4_us = kernel_us(lambda: lp4.conv(lws, lblob4, ly))
-    sm_R, sm_C = 16, 5120
-    small = {}
-    for bits in (8, 4):
-        sp = wq.DirectPlan(sm_R, 1, 1, sm_C, sm_C, lin_g, linear=True, weight_bits=bits)
-        sblob, sws, sy = sp.alloc_blob(), sp.alloc_workspace(), sp.alloc_output()
-        sp.weight_prepare(torch.randn(sm_C, sm_C, device="cuda") * 0.02, None, sblob)
-        sp.quantize(torch.randn(sm_R, sm_C, device="cuda"), sws)
-        small[f"w{bits}a8_gemm_us"] = round(kernel_us(lambda: sp.conv(sws, sblob, sy)), 2)
-    linear = dict(shape=f"{lin_R}x{lin_C}->{lin_C}, g={lin_g}", quantize_us=round(lq_us, 2),
-                  gemm_us=round(lc_us, 2),
-                  int8_tops=round(2 * lin_R * lin_C * lin_C / ((lq_us + lc_us) * 1e-6) / 1e12, 1),
-                  w4a8_gemm_us=round(lc4_us, 2),
-                  w4a8_tops=round(2 * lin_R * lin_C * lin_C / ((lq_us + lc4_us) * 1e-6) / 1e12, 1),
-                  small_batch=dict(shape=f"{sm_R}x{sm_C}->{sm_C}, g={lin_g}", **small))
+        # ---- the same quantized GEMM core as a linear layer (one tap): one attention-sized projection
+        lin_R, lin_C, lin_g = 4096, 1280, 64
+        lp = wq.DirectPlan(lin_R, 1, 1, lin_C, lin_C, lin_g, linear=True)
+        lblob, lws, ly = lp.alloc_blob(), lp.alloc_workspace(), lp.alloc_output()
+        lx = torch.randn(lin_R, lin_C, device="cuda")
+        lp.weight_prepare(torch.randn(lin_C, lin_C, device="cuda") * 0.02, None, lblob)
+        lq_us = kernel_us(lambda: lp.quantize(lx, lws))
+        lc_us = kernel_us(lambda: lp.conv(lws, lblob, ly))
+        lp4 = wq.DirectPlan(lin_R, 1, 1, lin_C, lin_C, lin_g, linear=True, weight_bits=4)
+        lblob4 = lp4.alloc_blob()
+        lp4.weight_prepare(torch.randn(lin_C, lin_C, device="cuda") * 0.02, None, lblob4)
+        lc4_us = kernel_us(lambda: lp4.conv(lws, lblob4, ly))
+        linear = dict(shape=f"{lin_R}x{lin_C}->{lin_C}, g={lin_g}", quantize_us=round(lq_us, 2),
+                      gemm_us=round(lc_us, 2),
+                      int8_tops=round(2 * lin_R * lin_C * lin_C / ((lq_us + lc_us) * 1e-6) / 1e12, 1),
+                      w4a8_gemm_us=round(lc4_us, 2),
+                      w4a8_tops=round(2 * lin_R * lin_C * lin_C / ((lq_us + lc4_us) * 1e-6) / 1e12, 1))
+
+        # ---- the other configurations as sub-blocks: whole-step time and TOPS, same launch choices
+        others = {}
+        if args.config == 5:
+            for c in (1, 2, 3, 4):
+                o_items = build_items(c)
+
+                def o_step():
+                    for it in o_items:
+                        it["plan"].forward(it["x"], it["blob"], it["ws"], it["y"])
+
+                o_t, _ = time_step(o_step, args.steps, args.warmup)
+                o_sec = min(o_t.values())
+                o_ops = sum(it["lay"].direct_ops for it in o_items)
+                others[f"configs[{c - 1}]"] = dict(
+                    convs_per_step=len(o_items), ms_per_step=round(o_sec * 1e3, 4),
+                    us_per_layer=round(o_sec * 1e6 / len(o_items), 2), value=round(o_ops / o_sec / 1e12, 2),
+                    unit="TOPS", launch=min(o_t, key=o_t.get),
+                    k2_variants=[it["plan"].k2_variant_name for it in o_items])
+                del o_items
+                torch.cuda.empty_cache()
 
     cpu_baseline = None
     if not args.no_cpu_baseline and args.config != 6:
@@ -392,18 +418,18 @@ def main():
                 M = oracle.contract(Xq, sX, Wq, sW, lay.group_size)
                 oracle.output_transform(M, AT, d.bias, lay.N, lay.H, lay.W, lay.m)
 
-        cpu_pass()
         t0 = time.perf_counter()
         passes = 0
-        while passes < 3 or (time.perf_counter() - t0 < 10 and passes < 50):
+        while passes < 1 or (time.perf_counter() - t0 < 10 and passes < 50):
             cpu_pass()
             passes += 1
         cpu_sec = (time.perf_counter() - t0) / passes
         cpu_ops = sum(l.direct_ops for l in layers)
         cpu_baseline = dict(value=round(cpu_ops / cpu_sec / 1e12, 5), unit="TOPS",
                             cores=oracle.threads(), kind="oracle",
-                            sample=f"{passes} forward passes over the full layer set (one conv per "
-                                   f"layer, weights prepared beforehand), {cpu_sec:.2f} s per pass",
+                            sample=f"{passes} forward pass(es) over one convolution per distinct layer shape "
+                                   f"({len(prepared)} of the step's {n_convs} convolutions, the same work per "
+                                   f"convolution), weights prepared beforehand, {cpu_sec:.2f} s per pass",
                             ms_per_pass=round(cpu_sec * 1e3, 1))
 
     out = dict(
@@ -411,14 +437,18 @@ def main():
                "(2*N*H*W*Cin*Cout*9 per layer / time); per-layer us in 'layers'",
         value=round(value, 2), unit="TOPS", n_gpus=1, steps=args.steps, warmup=args.warmup,
         ms_per_step=round(sec * 1e3, 4), us_per_layer=round(sec * 1e6 / n_convs, 2),
-        launch=launch_mode, ms_per_step_by_launch={k: round(v * 1e3, 4) for k, v in timings.items()},
+        launch=launch_mode, repeats=REPEATS, statistic="median of the repeats; value = fastest launch mode's median",
+        ms_per_step_by_launch={k: round(v * 1e3, 4) for k, v in timings.items()},
+        ms_per_step_min_max_by_launch=spread,
         higher_is_better=True, scaling="weak", vs_baseline=None, dtype="int8",
         data="synthetic",
-        config=dict(workload=f"configs[{args.config - 1}]: " + "; ".join(l.name for l in layers),
+        config=dict(workload=f"configs[{args.config - 1}]: " + "; ".join(
+                        l.name + (f" x{l.repeat} chained" if l.repeat > 1 else "") for l in layers),
                     winograd=f"F({layers[0].m},3)", group_size=layers[0].group_size,
-                    batch=layers[0].N, convs_per_step=n_convs),
-        roofline=roofline, cpu_baseline=cpu_baseline, direct_conv_same_layers=direct,
-        cold_cache=cold, quantized_linear_layer=linear,
+                    batch=layers[0].N, convs_per_step=n_convs,
+                    resident_mb=round(footprint / 1e6, 1)),
+        roofline=roofline, ceiling=ceiling, cpu_baseline=cpu_baseline, direct_conv_same_layers=direct,
+        quantized_linear_layer=linear, other_configs=others,
         with_offline_stage=dict(value=round(direct_ops / sec_off / 1e12, 2), unit="TOPS",
                                 ms_per_step=round(sec_off * 1e3, 4)),
         layers=per_layer)

@@ -93,6 +93,17 @@ def quantize_group(v):
     return q, np.float32(s)
 
 
+def quantize_group_literal(v):
+    """The quantizer equation with a division per element (see the C function): for measuring the
+    distance of the library's reading from the text, nothing else."""
+    v = _f32(v).ravel()
+    q = np.empty(v.size, dtype=np.int8)
+    L = _load()
+    L.oracle_quantize_group_literal.restype = ctypes.c_float
+    s = L.oracle_quantize_group_literal(_p(v), int(v.size), _p(q))
+    return q, np.float32(s)
+
+
 def weight_transform_quant(w, G, m: int, g: int, want_float: bool = False):
     w, G = _f32(w), _f32(G)
     Cout, Cin = w.shape[:2]

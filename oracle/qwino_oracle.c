@@ -208,6 +208,31 @@ float oracle_quantize_group_bits(const float *v, int count, int bits, int8_t *q)
     return quantize_group_q(v, 1, count, q, 1, qmax_of(bits));
 }
 
+/* The quantizer equation of Section "Related work" read to the letter, x_int =
+ * clamp(round(x / s)) with s = a / 127 and one IEEE division per element.  Not used by any
+ * pipeline here: it only measures how far the reading x * (127 / a) of quantize_group_q is
+ * from the text (the two differ where x / s falls within a rounding error of a half-integer). */
+float oracle_quantize_group_literal(const float *v, int count, int8_t *q)
+{
+    float a = 0.0f;
+    for (int k = 0; k < count; ++k) {
+        float t = fabsf(v[k]);
+        if (t > a) a = t;
+    }
+    if (!(a >= 127.0f * FLT_MIN)) {
+        for (int k = 0; k < count; ++k) q[k] = 0;
+        return 0.0f;
+    }
+    const float s = a / 127.0f;
+    for (int k = 0; k < count; ++k) {
+        float z = rintf(v[k] / s);
+        if (z > 127.0f) z = 127.0f;
+        if (z < -127.0f) z = -127.0f;
+        q[k] = (int8_t)z;
+    }
+    return s;
+}
+
 /* -------------------------------------------------- stage 4 (offline) */
 void oracle_weight_transform_quant(const float *w, const float *G, int Cin, int Cout,
                                    int m, int g, int8_t *Wq, float *sW, float *Wf)

@@ -268,3 +268,30 @@ def test_power_of_two_row_scales_change_nothing_but_the_stored_scales(m):
     assert np.array_equal(r1["sX"], r0["sX"] * fB[:, None, None])
     assert np.array_equal(r1["sW"], r0["sW"] * fG[:, None, None])
     assert np.array_equal(r0["y64"], r1["y64"])
+
+
+def test_reciprocal_reading_of_the_quantizer_against_the_literal_division():
+    """The library and the oracle evaluate x / s as x * (127 / a) (one division per group).  On
+    the Winograd-domain activations and weights of config 1 this differs from the division the
+    quantizer equation writes only in codes where x / s lies within a rounding error of a
+    half-integer: a few codes in a million, each by exactly one step, and the scales are the
+    same numbers.  (The count is quoted in the design doc.)"""
+    from paper_2412_19867_amd import workloads
+    d = workloads.make_layer_data(workloads.CONFIGS[1][0])
+    lay = d.layer
+    AT, BT, G = (M.astype(np.float32) for M in ct.standard_matrices(lay.m))
+    _, _, Xf = oracle.input_transform_quant(d.x, BT, lay.m, lay.group_size, want_float=True)
+    _, _, Wf = oracle.weight_transform_quant(d.w, G, lay.m, lay.group_size, want_float=True)
+    total = differ = 0
+    for tensor in (Xf, Wf):
+        groups = np.ascontiguousarray(tensor.reshape(-1, lay.group_size))
+        for row in groups[:: max(1, len(groups) // 20000)]:          # ~20000 groups of each tensor
+            qa, sa = oracle.quantize_group(row)
+            ql, sl = oracle.quantize_group_literal(row)
+            assert sa == sl
+            delta = np.abs(qa.astype(np.int32) - ql.astype(np.int32))
+            assert delta.max() <= 1
+            differ += int(np.count_nonzero(delta))
+            total += row.size
+    print(f"codes that differ from the literal division: {differ} of {total} ({differ / total:.2e})")
+    assert differ / total < 1e-4

@@ -16,17 +16,18 @@
 // The compiler does not order LDS reads after such loads by itself: the loop does it by hand
 // (a counted wait on the wave's own loads, then the workgroup barrier).
 // A wave issues at most one instruction every four cycles or so, and with the output
-// transform's state in registers only two waves fit a SIMD, so the loop is written to keep the
-// instruction count per step down: the ring is unrolled (every LDS address is an immediate), the
+// transform's state in registers only two or three waves fit a SIMD, so the loop is written to
+// keep the instruction count per step down: the ring is unrolled (every LDS address is an immediate), the
 // loader's cursor is branch-free scalar arithmetic, and the int32 dump of the debug entry point is
 // a template switch of the same kernel, not a test inside the loop.
 // A wave's state per output element is
 //     int32 block (fresh per group)  ->  M += float(block) * sW[o] * sX[tile]    (group end)
 //     R[b]    += A^T[b][j] * M                                                   (end of tap (i,j))
 //     Y[a][b] += A^T[a][i] * R[b]                                                (end of tap row i)
-// i.e. 1 + m + m*m floats, never the n*n Winograd-domain values.  With one K-step per group the
-// loop is software-pipelined: the MFMAs of step s are issued before the vector-ALU
-// dequantization of step s-1, so the matrix core runs under it.
+// i.e. 1 + m + m*m floats, never the n*n Winograd-domain values.  A wave dequantizes a step's
+// blocks right after their MFMAs; a second set of accumulators that would let the next step's
+// MFMAs run under the dequantization costs 16 registers and measured slower than what the extra
+// resident workgroup does with them (MFMA and vector-ALU time add up on a SIMD either way).
 //
 // Two forms:
 //   FULL  a workgroup walks all n*n taps and stores y (NHWC, ragged edge masked): one kernel,
@@ -93,7 +94,7 @@ __device__ __forceinline__ void wait_loads_and_barrier() {
 // NS = stages of the LDS ring.  DUMP: the debug entry point's instance, which also stores the
 // int32 group sums.
 template <int M, bool K64, bool CPG1, bool WIDE, bool FULL, bool DUMP, int NWO, int NWT, int BN, int BM, int NS>
-__global__ __launch_bounds__(64 * NWO * NWT) void k_wino_lds(const LArgs a) {
+__global__ __launch_bounds__(64 * NWO * NWT, 2) void k_wino_lds(const LArgs a) {
     constexpr int n = M + 2, NW = NWO * NWT;
     constexpr int KSTEP = K64 ? 64 : 32, KB = KSTEP / 4;
     constexpr int BLK = 16 * KSTEP;                    // bytes of one K-step of a 16-row block
@@ -109,15 +110,12 @@ __global__ __launch_bounds__(64 * NWO * NWT) void k_wino_lds(const LArgs a) {
     constexpr int STAGE = OPB + 768;
     constexpr int D = NS - 2;                          // steps in flight
     constexpr int LPS = LW + 1;                        // loads per wave and step
-    static_assert(NS >= 4 && NS % 2 == 0, "ring size (the accumulators alternate with the step's parity)");
+    static_assert(NS >= 4 && NS % 2 == 0, "ring size (the operand register sets alternate with the step's parity)");
     static_assert(NW >= 2 && NSW <= 64 && NSX <= 64, "wave 0 fetches the weight scales, wave 1 the activation scales");
     static_assert(K64 || OBW % 2 == 0, "a wave's 64 chunks must not straddle weights and activations");
     static_assert(D * LPS < 64, "the wait counts loads");
     __shared__ __attribute__((aligned(16))) char ring[NS * STAGE];
 
-#ifdef WQ_TIMING
-    const long long tm0 = __builtin_readcyclecounter();
-#endif
     const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15, q = lane >> 4;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6), wo = w % NWO, wt = w / NWO;
     // Workgroup ids go round-robin over the 8 XCDs, whose L2s are private: XCD x takes the
@@ -206,7 +204,7 @@ __global__ __launch_bounds__(64 * NWO * NWT) void k_wino_lds(const LArgs a) {
     };
 
     // ---- per-element state ----
-    v4i acc[2][BN][BM];     // one K-step per group: the two sets alternate with the step's parity
+    v4i acc[BN][BM];
     float4 Mc[BN][BM];
     double Mt[BN][BM][4];
     float4 R[M][BN][BM];
@@ -215,7 +213,7 @@ __global__ __launch_bounds__(64 * NWO * NWT) void k_wino_lds(const LArgs a) {
     for (int no = 0; no < BN; ++no)
 #pragma unroll
         for (int nt = 0; nt < BM; ++nt) {
-            acc[0][no][nt] = acc[1][no][nt] = v4i{0, 0, 0, 0};
+            acc[no][nt] = v4i{0, 0, 0, 0};
             Mc[no][nt] = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
             for (int r = 0; r < 4; ++r) Mt[no][nt][r] = 0.0;
@@ -228,11 +226,10 @@ __global__ __launch_bounds__(64 * NWO * NWT) void k_wino_lds(const LArgs a) {
                     for (int b = 0; b < M; ++b) Y[aa][b][no][nt] = make_float4(0.f, 0.f, 0.f, 0.f);
             }
         }
-    // The compute cursor (uniform).  With one K-step per group the loop calls finish_group one
-    // step late, the first time on zeros before any group exists: the counters start one group back.
-    int g_left = groups + (CPG1 ? 1 : 0), in_chunk = CPG1 ? -1 : 0;   // groups left in the tap; groups in the fp32 chunk
-    int i_cp = FULL ? 0 : row_i, j_cp = 0;                            // the tap being reduced
-    int gam_cp = CPG1 ? -1 : 0;                                       // its group (the dump's index)
+    // The compute cursor (uniform).
+    int g_left = groups, in_chunk = 0;        // groups left in the tap; groups in the fp32 chunk
+    int i_cp = FULL ? 0 : row_i, j_cp = 0;    // the tap being reduced
+    int gam_cp = 0;                           // its group (the dump's index)
     float atc[M], atr[M];   // column j_cp of A^T (for R), column i_cp of A^T (for Y)
 #pragma unroll
     for (int b = 0; b < M; ++b) {
@@ -253,8 +250,7 @@ __global__ __launch_bounds__(64 * NWO * NWT) void k_wino_lds(const LArgs a) {
                 Mc[no][nt].w = __builtin_fmaf((float)ac[no][nt][3], sw[no].w * sx[nt], Mc[no][nt].w);
                 if constexpr (DUMP) {
                     const int v[4] = {ac[no][nt][0], ac[no][nt][1], ac[no][nt][2], ac[no][nt][3]};
-                    if (gam_cp >= 0)
-                        wq_dump_store(a.dump, i_cp * n + j_cp, (tb0 + BM * wt + nt) * 16 + l16, gam_cp, groups,
+                    wq_dump_store(a.dump, i_cp * n + j_cp, (tb0 + BM * wt + nt) * 16 + l16, gam_cp, groups,
                                       (ob0 + BN * wo + no) * 16 + 4 * q, a.Cout, a.T, v);
                 }
             }
@@ -272,11 +268,7 @@ __global__ __launch_bounds__(64 * NWO * NWT) void k_wino_lds(const LArgs a) {
                     Mc[no][nt] = make_float4(0.f, 0.f, 0.f, 0.f);
                 }
         }
-#ifdef WQ_EXP_NOFOLD
-        if (--g_left == -12345) {
-#else
         if (--g_left == 0) {   // end of tap (i_cp, j_cp)
-#endif
             g_left = groups;
             in_chunk = 0;
             if constexpr (DUMP) gam_cp = 0;
@@ -383,9 +375,8 @@ __global__ __launch_bounds__(64 * NWO * NWT) void k_wino_lds(const LArgs a) {
     // Step s: request step s + D into stage (s + D) % NS = (s - 2) % NS, which every wave
     // finished reading before it arrived at the barrier of step s - 1; wait until this wave's
     // loads of step s + 1 have landed (all but the D - 1 newer steps' loads); barrier:
-    // everybody's have.  The operands of step s + 1 are then read into the other register set
-    // while the MFMAs of step s run, and with one K-step per group the dequantization of step
-    // s - 1 runs under them as well.
+    // everybody's have.  The operands (and, with one K-step per group, the scales) of step s + 1
+    // are then read into the other register set while the MFMAs and the dequantization of step s run.
 #pragma unroll
     for (int d = 0; d < D; ++d) issue(d);
     v4f swS[2][BN] = {};
@@ -393,48 +384,30 @@ __global__ __launch_bounds__(64 * NWO * NWT) void k_wino_lds(const LArgs a) {
     v4i avS[2][BN], bvS[2][BM];
     wait_loads_and_barrier<DUMP ? 0 : (D - 1) * LPS>();   // (the dump's stores are counted too: wait for all)
     read_operands(0, avS[0], bvS[0]);
-#ifdef WQ_TIMING
-    const long long tm1 = __builtin_readcyclecounter();
-#endif
+    if constexpr (CPG1) read_scales(0, swS[0], sxS[0]);
     for (int sb = 0; sb < NSTEPS; sb += NS) {
 #pragma unroll
         for (int v = 0; v < NS; ++v) {
             if (sb + v >= NSTEPS) break;   // NSTEPS is even but need not be a multiple of NS
             const int u = v & 1;
-#ifndef WQ_EXP_NOLOAD
             issue((v + D) % NS);
-#endif
-#ifndef WQ_EXP_NOBAR
             wait_loads_and_barrier<DUMP ? 0 : (D - 1) * LPS>();
-#endif
-#ifndef WQ_EXP_NOREAD
             read_operands((v + 1) % NS, avS[u ^ 1], bvS[u ^ 1]);   // past the last step: read, never used
-#endif
             if constexpr (CPG1) {
-#ifndef WQ_EXP_NOREAD
-                read_scales(v, swS[u], sxS[u]);
-#endif
-#ifndef WQ_EXP_NOMFMA
-                mfma_blocks(acc[u], avS[u], bvS[u], true);
-#endif
-#ifndef WQ_EXP_NODEQ
-                finish_group(acc[u ^ 1], swS[u ^ 1], sxS[u ^ 1]);   // the previous step's group
-#endif
+                mfma_blocks(acc, avS[u], bvS[u], true);
+                read_scales((v + 1) % NS, swS[u ^ 1], sxS[u ^ 1]);
+                finish_group(acc, swS[u], sxS[u]);
             } else {
                 const int s = sb + v;
                 const bool first = (s & cpg_mask) == 0, last = ((s + 1) & cpg_mask) == 0;
-                mfma_blocks(acc[0], avS[u], bvS[u], first);
+                mfma_blocks(acc, avS[u], bvS[u], first);
                 if (last) {
                     read_scales(v, swS[0], sxS[0]);
-                    finish_group(acc[0], swS[0], sxS[0]);
+                    finish_group(acc, swS[0], sxS[0]);
                 }
             }
         }
     }
-    if constexpr (CPG1) finish_group(acc[1], swS[1], sxS[1]);   // NSTEPS is even: the last step sat in set 1
-#ifdef WQ_TIMING
-    const long long tm2 = __builtin_readcyclecounter();
-#endif
 
     // ---- epilogue ----
     if constexpr (FULL) {
@@ -490,13 +463,6 @@ __global__ __launch_bounds__(64 * NWO * NWT) void k_wino_lds(const LArgs a) {
             }
         }
     }
-#ifdef WQ_TIMING
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    if (FULL && tid == 0) {
-        long long *tmo = reinterpret_cast<long long *>(a.Rbuf) + (size_t)blockIdx.x * 4;
-        tmo[0] = tm0; tmo[1] = tm1; tmo[2] = tm2; tmo[3] = __builtin_readcyclecounter();
-    }
-#endif
 }
 
 template <int M, bool K64, bool CPG1, bool WIDE, bool FULL, bool DUMP, int NWO, int NWT, int BN, int BM, int NS>
@@ -531,11 +497,7 @@ void launch_variant(const LArgs &a, hipStream_t s, int variant) {
             launch_tile<M, K64, CPG1, WIDE, true, DUMP, 4, 2 / FBM, 1, FBM, 8>(a, s);
             break;
         case WQ_K2_LDS_ROW_64x64:
-#ifdef WQ_ROW_CFG
-            launch_tile<M, K64, CPG1, WIDE, false, DUMP, WQ_ROW_CFG>(a, s);
-#else
-            launch_tile<M, K64, CPG1, WIDE, false, DUMP, 2, 2, 2, 2, 8>(a, s);
-#endif
+            launch_tile<M, K64, CPG1, WIDE, false, DUMP, 2, 2, 2, 2, 6>(a, s);   // 3 workgroups' rings per CU
             break;
         default:   // WQ_K2_LDS_ROW_32x64
             launch_tile<M, K64, CPG1, WIDE, false, DUMP, 4, 1, 1, 2, 8>(a, s);
@@ -547,7 +509,7 @@ void launch_variant(const LArgs &a, hipStream_t s, int variant) {
 template <int M, bool DUMP>
 hipError_t launch_lds_m(const wq_plan *p, hipStream_t s, const LArgs &a) {
     const bool k64 = p->kstep == 64, cpg1 = p->g == p->kstep;
-    const bool wide = p->groups > 8;   // fp64 chunk totals where a tap reduces more than 8 groups
+    const bool wide = p->groups > 16;   // fp64 chunk totals where a tap reduces more than 16 groups
     const int v = p->k2_variant;
     if (!k64) {
         if (wide) launch_variant<M, false, true, true, DUMP>(a, s, v);

@@ -171,6 +171,13 @@ bool variant_applicable(const wq_plan *p, int v) {
 }
 
 int default_k2_variant(const wq_plan *p) {
+    // The row form with operand tiles shared through LDS: measured ahead of the others where its
+    // workgroups (64 tiles x 64 channels x one tap row) fill the GPU once at two to three per CU
+    // and each of them walks a reduction long enough to pay for the second kernel.
+    if (variant_applicable(p, WQ_K2_LDS_ROW_64x64) && p->g == p->kstep && p->groups >= 8) {
+        const long wgs = (long)((p->T_pad + 63) / 64) * ((p->Cout_pad + 63) / 64) * (p->m + 2);
+        if (wgs >= 384 && wgs <= 768) return WQ_K2_LDS_ROW_64x64;
+    }
     // With few tiles the Winograd-domain result is small next to the operands, and a tiled GEMM
     // per tap plus a separate output transform beats the fused kernel; so it does for very wide
     // layers and for groups of 128 and more, where the fused kernel's register tiles re-read the

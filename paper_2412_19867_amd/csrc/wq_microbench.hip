@@ -26,7 +26,7 @@ __device__ __forceinline__ void opaque(T &v) {
 }
 
 template <int MODE, bool K64, int KPG, int NB>
-__global__ __launch_bounds__(256) void k_h1(const int *__restrict__ seed, float *__restrict__ out,
+__global__ __launch_bounds__(256, 2) void k_h1(const int *__restrict__ seed, float *__restrict__ out,
                                            long long *__restrict__ cycles, int iters) {
     constexpr int NA = NB / 2;   // the wave's blocks are NA x 2: NA weight operands, 2 activation operands
     const int tid = threadIdx.x;

@@ -106,6 +106,9 @@ def main():
     ap.add_argument("--only-steps", action="store_true",
                     help="launch warmup+steps steps eagerly, print the launch count and exit (for counter "
                          "runs: every dispatch in the process then belongs to a step)")
+    ap.add_argument("--k2-variant", default=None,
+                    help="force this kernel variant of stages 2+3 on every layer it applies to (for "
+                         "before/after profiles; the default is the plan's own choice per layer)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a 256 MiB device-to-device copy three times (known HBM traffic, "
                          "used to calibrate the FETCH_SIZE / WRITE_SIZE counters) and exit")
@@ -142,6 +145,11 @@ def main():
                 AT, BT, G = wq.scaled_transforms(lay.m, d.u_B, d.u_G)
                 kw = dict(AT=AT, BT=BT, G=G)
             plan = wq.Plan(lay.N, lay.H, lay.W, lay.Cin, lay.Cout, lay.m, lay.group_size, **kw)
+            if args.k2_variant:
+                try:
+                    plan.tune(0, args.k2_variant)
+                except wq.WqError:
+                    pass   # not applicable to this layer: the plan's own choice stays
             x = torch.from_numpy(d.x).cuda()
             w, b = torch.from_numpy(d.w).cuda(), torch.from_numpy(d.bias).cuda()
             for r in range(lay.repeat):
@@ -257,8 +265,8 @@ def main():
             cache[k] = kernel_us(fn)
         return cache[k]
 
-    FIRST_KERNEL = {"fused": "k_contract_output", "gemm": "k_gemm_dequant", "lds_full": "k_wino_lds_full",
-                    "lds_row": "k_wino_lds_row"}
+    FIRST_KERNEL = {"fused": "k_contract_output", "gemm": "k_gemm_dequant", "lds_full": "k_wino_lds",
+                    "lds_row": "k_wino_lds"}
     SECOND_KERNEL = {"gemm": "k_output_transform", "lds_row": "k_row_finish"}
 
     per_layer, kernels = [], {}
@@ -452,6 +460,8 @@ def main():
         with_offline_stage=dict(value=round(direct_ops / sec_off / 1e12, 2), unit="TOPS",
                                 ms_per_step=round(sec_off * 1e3, 4)),
         layers=per_layer)
+    if args.k2_variant:
+        out["config"]["k2_variant_forced"] = args.k2_variant
     print(json.dumps(out))
 
 

@@ -185,15 +185,15 @@ template <int M, int TR, int I0, bool SPARSE>
 __device__ __forceinline__ void input_body(const wq_xf &xf, const float *__restrict__ x,
                                            int8_t *__restrict__ Xq, float *__restrict__ sX, int H,
                                            int W, int Cin, int TH, int TW, int T, int T_pad,
-                                           int log2k, int kstep_log2, unsigned x_bytes,
+                                           int log2k, int kstep_log2, unsigned x_bytes, int bid,
                                            uint4 (*amax_s)[16], float (*r_s)[16], char *codes_s) {
     constexpr int n = M + 2, NT = TR * n;
     using Pat = wq_pattern<M>;
     const int tid = threadIdx.x, row = tid >> 4, l16 = tid & 15;
     const int k = 1 << log2k;
     const int CC = Cin >> 5, groups = CC >> log2k;
-    // blockIdx.x -> (16-tile block rb, sub-block of 16/k tiles, group)
-    const int rb = blockIdx.x / CC, rem = blockIdx.x % CC;
+    // workgroup -> (16-tile block rb, sub-block of 16/k tiles, group)
+    const int rb = bid / CC, rem = bid % CC;
     const int sub = rem / groups, gam = rem % groups;
     const int row16 = sub * (16 >> log2k) + (row >> log2k);      // tile inside the 16-tile block
     const int chunk = gam * k + (row & (k - 1));
@@ -282,14 +282,23 @@ __global__ __launch_bounds__(256) void k_input_transform(wq_xf xf, const float *
                                                          float *__restrict__ sX, int H, int W,
                                                          int Cin, int TH, int TW, int T, int T_pad,
                                                          int log2k, int kstep_log2,
-                                                         unsigned x_bytes) {
+                                                         unsigned x_bytes, int total, int per_xcd) {
     constexpr int n = M + 2;
-    __shared__ uint4 amax_s[TR * n][16];
+    // Workgroup ids go round-robin over the 8 XCDs, whose L2s are private: XCD x takes the
+    // workgroups [x * per_xcd, (x + 1) * per_xcd) of the tile order, a band of whole tile rows,
+    // so that the two input rows that vertically adjacent tiles share are found in that L2.
+    const int bid = (int)(blockIdx.x & 7u) * per_xcd + (int)(blockIdx.x >> 3);
+    if (bid >= total) return;   // the whole workgroup leaves, before any barrier
+    // The abs-max words are dead once the scales exist (the barrier behind the scale pass), the
+    // codes are staged after it: both live in the same LDS bytes, which lets one more workgroup
+    // onto a CU.
     __shared__ float r_s[TR * n][16];
     __shared__ __attribute__((aligned(16))) char codes_s[TR * n * kTapStride];
+    static_assert(sizeof(uint4) * 16 <= kTapStride, "the abs-max rows fit under the code rows");
+    uint4 (*amax_s)[16] = reinterpret_cast<uint4 (*)[16]>(codes_s);
 #define WQ_BODY(I0)                                                                            \
     input_body<M, TR, (I0), SPARSE>(xf, x, Xq, sX, H, W, Cin, TH, TW, T, T_pad, log2k, kstep_log2, \
-                                x_bytes, amax_s, r_s, codes_s)
+                                x_bytes, bid, amax_s, r_s, codes_s)
     // uniform branch: which block of TR tap rows this workgroup forms
     constexpr int NY = n / TR;
     static_assert(NY * TR == n && NY <= 8, "unsupported tap-row split");
@@ -437,15 +446,16 @@ int ilog2(int v) {
 
 template <int M, int TR>
 hipError_t launch_input_rows(const wq_plan *p, hipStream_t s, const float *x, int8_t *Xq, float *sX) {
-    const dim3 grid((unsigned)((p->T_pad / 16) * (p->Cin / 32)), (M + 2) / TR), block(256);
+    const int total = (p->T_pad / 16) * (p->Cin / 32), per_xcd = (total + 7) / 8;
+    const dim3 grid((unsigned)per_xcd * 8u, (M + 2) / TR), block(256);
     const int log2k = ilog2(p->g / 32), kstep_log2 = p->kstep == 32 ? 5 : 6;
     const unsigned x_bytes = (unsigned)((size_t)p->N * p->H * p->W * p->Cin * 4);
     if (p->sparse_bt)
         hipLaunchKernelGGL((k_input_transform<M, TR, true>), grid, block, 0, s, p->xf, x, Xq, sX, p->H,
-                           p->W, p->Cin, p->TH, p->TW, p->T, p->T_pad, log2k, kstep_log2, x_bytes);
+                           p->W, p->Cin, p->TH, p->TW, p->T, p->T_pad, log2k, kstep_log2, x_bytes, total, per_xcd);
     else
         hipLaunchKernelGGL((k_input_transform<M, TR, false>), grid, block, 0, s, p->xf, x, Xq, sX, p->H,
-                           p->W, p->Cin, p->TH, p->TW, p->T, p->T_pad, log2k, kstep_log2, x_bytes);
+                           p->W, p->Cin, p->TH, p->TW, p->T, p->T_pad, log2k, kstep_log2, x_bytes, total, per_xcd);
     return hipGetLastError();
 }
 

@@ -266,8 +266,8 @@ def main():
         return cache[k]
 
     FIRST_KERNEL = {"fused": "k_contract_output", "gemm": "k_gemm_dequant", "lds_full": "k_wino_lds",
-                    "lds_row": "k_wino_lds"}
-    SECOND_KERNEL = {"gemm": "k_output_transform", "lds_row": "k_row_finish"}
+                    "lds_row": "k_wino_lds", "lds_tap": "k_wino_lds"}
+    SECOND_KERNEL = {"gemm": "k_output_transform", "lds_row": "k_row_finish", "lds_tap": "k_output_transform"}
 
     per_layer, kernels = [], {}
 
@@ -306,7 +306,7 @@ def main():
             b_us = per_plan(it, "k2b", lambda: plan.contract_output_part(it["ws"], it["blob"], it["y"], 2))
             # the fp32 intermediate (the n*n Winograd-domain products, or the n*m row sums of the row
             # form) is written by the first kernel and read back by the second
-            per_elem = lay.n ** 2 if fam == "gemm" else lay.n * lay.m
+            per_elem = lay.n * lay.m if fam == "lds_row" else lay.n ** 2
             mid_bytes = 4 * per_elem * lay.tiles * lay.Cout
             y_bytes = 4 * lay.N * lay.H * lay.W * lay.Cout
             account(FIRST_KERNEL[fam], a_us, k2_bytes(lay) - y_bytes + mid_bytes)

@@ -15,7 +15,7 @@ hipError_t wq_launch_contract(const wq_plan *p, hipStream_t s, const int8_t *Xq,
                               float *y, const wq_dump &dump, int parts) {
     if (wq_is_gemm_variant(p->k2_variant))
         return wq_launch_contract_unfused(p, s, Xq, sX, Wq, sW, bias, Mbuf, y, parts, dump);
-    if (wq_is_lds_full_variant(p->k2_variant) || wq_is_lds_row_variant(p->k2_variant))
+    if (wq_is_lds_variant(p->k2_variant))
         return wq_launch_contract_lds(p, s, Xq, sX, Wq, sW, bias, Mbuf, y, dump, parts);
     if (!(parts & 1)) return hipSuccess;   // the fused kernel is the variant's only one
     switch (p->m) {

@@ -94,6 +94,9 @@ hipError_t wq_launch_contract_lds(const wq_plan *p, hipStream_t s, const int8_t 
         if (p->m == 4) e = dump.P ? wq_launch_lds_m4_dump(p, s, &a) : wq_launch_lds_m4(p, s, &a);
         else e = dump.P ? wq_launch_lds_m6_dump(p, s, &a) : wq_launch_lds_m6(p, s, &a);
     }
-    if (e != hipSuccess || !wq_is_lds_row_variant(p->k2_variant) || !(parts & 2)) return e;
+    if (e != hipSuccess || !(parts & 2)) return e;
+    if (wq_is_lds_tap_variant(p->k2_variant))   // the output-transform kernel of the GEMM form reads the same M
+        return wq_launch_contract_unfused(p, s, Xq, sX, Wq, sW, bias, Mbuf, y, 2, dump);
+    if (!wq_is_lds_row_variant(p->k2_variant)) return e;
     return p->m == 4 ? launch_finish<4>(p, s, a) : launch_finish<6>(p, s, a);
 }

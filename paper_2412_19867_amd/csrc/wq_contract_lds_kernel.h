@@ -37,6 +37,10 @@
 //         (m floats per element instead of the n a row of M would take) to the workspace;
 //         k_row_finish then forms y = sum_i A^T[a][i] R_i[b] + bias.  n times the workgroups,
 //         for layers with few tiles.
+//   TAP   a workgroup reduces ONE tap and stores its fp32 Winograd-domain products M
+//         [T_pad][n*n][Cout_pad] to the workspace for the separate output-transform kernel:
+//         n*n times the workgroups, each short and with no output-transform state in registers
+//         (four waves per SIMD), for layers with very few tiles and long reductions.
 #pragma once
 
 #include "wq_internal.h"
@@ -58,7 +62,7 @@ struct LArgs {
     const float *sW;
     const float *bias;
     float *y;      // FULL: the layer's output
-    float *Rbuf;   // ROW: row sums [T_pad][n][m][Cout_pad] in the workspace
+    float *Rbuf;   // ROW: row sums [T_pad][n][m][Cout_pad] in the workspace; TAP: M [T_pad][n*n][Cout_pad]
     wq_dump dump;  // debug calls: where to store the int32 group sums
     int H, W, Cin, Cout, TH, TW, T, T_pad, Cout_pad, log2g;
     // workgroup tiles along channels and tiles, the number of workgroups, the share of each XCD,
@@ -93,8 +97,10 @@ __device__ __forceinline__ void wait_loads_and_barrier() {
 // NWO x NWT waves (along channels x along tiles), each a BN x BM arrangement of 16x16 blocks;
 // NS = stages of the LDS ring.  DUMP: the debug entry point's instance, which also stores the
 // int32 group sums.
-template <int M, bool K64, bool CPG1, bool WIDE, bool FULL, bool DUMP, int NWO, int NWT, int BN, int BM, int NS>
+template <int M, bool K64, bool CPG1, bool WIDE, bool FULL, bool DUMP, int NWO, int NWT, int BN, int BM, int NS, bool TAP = false>
 __global__ __launch_bounds__(64 * NWO * NWT, 2) void k_wino_lds(const LArgs a) {
+    static_assert(!(FULL && TAP), "one form at a time");
+    constexpr int NTAPS = FULL ? (M + 2) * (M + 2) : (TAP ? 1 : M + 2);   // taps a workgroup walks
     constexpr int n = M + 2, NW = NWO * NWT;
     constexpr int KSTEP = K64 ? 64 : 32, KB = KSTEP / 4;
     constexpr int BLK = 16 * KSTEP;                    // bytes of one K-step of a 16-row block
@@ -124,7 +130,7 @@ __global__ __launch_bounds__(64 * NWO * NWT, 2) void k_wino_lds(const LArgs a) {
     const int logical = (int)(blockIdx.x & 7u) * a.per_xcd + (int)(blockIdx.x >> 3);
     if (logical >= a.total) return;   // the whole workgroup leaves, before any barrier
     int row_i = 0, rem = logical;
-    if constexpr (!FULL) {
+    if constexpr (!FULL) {   // row_i: the tap row (ROW) or the tap (TAP) of this workgroup
         const int per_row = a.nOBt * a.nTBt;
         row_i = logical / per_row;
         rem = logical - row_i * per_row;
@@ -155,8 +161,8 @@ __global__ __launch_bounds__(64 * NWO * NWT, 2) void k_wino_lds(const LArgs a) {
     const unsigned planeW = (unsigned)Cout_pad * Cin, planeX = (unsigned)T_pad * Cin;
     const unsigned planeSX = (unsigned)T_pad * groups * 4;
     const unsigned stepSW = (unsigned)Cout_pad * 4;   // a tap's weight scales are groups * stepSW bytes: taps are contiguous
-    const unsigned t_first = FULL ? 0u : (unsigned)(row_i * n), t_last = t_first + (FULL ? n * n : n) - 1;
-    const int NSTEPS = (FULL ? n * n : n) * cps;
+    const unsigned t_first = FULL ? 0u : (unsigned)(TAP ? row_i : row_i * n), t_last = t_first + NTAPS - 1;
+    const int NSTEPS = NTAPS * cps;
     unsigned vop[LW], oOp[LW], jumpOp[LW], lastOp[LW];
     bool is_w[LW];
 #pragma unroll
@@ -183,8 +189,8 @@ __global__ __launch_bounds__(64 * NWO * NWT, 2) void k_wino_lds(const LArgs a) {
     const unsigned stepSc = w == 0 ? stepSW : 64u;                                  // per group
     const unsigned jumpSc = w == 0 ? 0u : planeSX - (unsigned)groups * 64u;         // per tap
     unsigned oSc = w == 0 ? t_first * (unsigned)groups * stepSW : t_first * planeSX;
-    const unsigned lastSc = oSc + (w == 0 ? (unsigned)(FULL ? n * n : n) * groups * stepSW - stepSW
-                                          : (unsigned)((FULL ? n * n : n) - 1) * planeSX + (unsigned)(groups - 1) * 64u);
+    const unsigned lastSc = oSc + (w == 0 ? (unsigned)NTAPS * groups * stepSW - stepSW
+                                          : (unsigned)(NTAPS - 1) * planeSX + (unsigned)(groups - 1) * 64u);
     int k_ld = 0;
 
     auto issue = [&](int stage) {   // request the cursor's step into ring stage `stage` (a constant after unrolling)
@@ -207,7 +213,7 @@ __global__ __launch_bounds__(64 * NWO * NWT, 2) void k_wino_lds(const LArgs a) {
     v4i acc[BN][BM];
     float4 Mc[BN][BM];
     double Mt[BN][BM][4];
-    float4 R[M][BN][BM];
+    float4 R[TAP ? 1 : M][BN][BM];
     float4 Y[FULL ? M : 1][FULL ? M : 1][BN][BM];
 #pragma unroll
     for (int no = 0; no < BN; ++no)
@@ -218,7 +224,7 @@ __global__ __launch_bounds__(64 * NWO * NWT, 2) void k_wino_lds(const LArgs a) {
 #pragma unroll
             for (int r = 0; r < 4; ++r) Mt[no][nt][r] = 0.0;
 #pragma unroll
-            for (int b = 0; b < M; ++b) R[b][no][nt] = make_float4(0.f, 0.f, 0.f, 0.f);
+            for (int b = 0; b < (TAP ? 1 : M); ++b) R[b][no][nt] = make_float4(0.f, 0.f, 0.f, 0.f);
             if constexpr (FULL) {
 #pragma unroll
                 for (int aa = 0; aa < M; ++aa)
@@ -228,7 +234,7 @@ __global__ __launch_bounds__(64 * NWO * NWT, 2) void k_wino_lds(const LArgs a) {
         }
     // The compute cursor (uniform).
     int g_left = groups, in_chunk = 0;        // groups left in the tap; groups in the fp32 chunk
-    int i_cp = FULL ? 0 : row_i, j_cp = 0;    // the tap being reduced
+    int i_cp = FULL ? 0 : (TAP ? row_i / n : row_i), j_cp = TAP ? row_i % n : 0;    // the tap being reduced
     int gam_cp = 0;                           // its group (the dump's index)
     float atc[M], atr[M];   // column j_cp of A^T (for R), column i_cp of A^T (for Y)
 #pragma unroll
@@ -268,7 +274,7 @@ __global__ __launch_bounds__(64 * NWO * NWT, 2) void k_wino_lds(const LArgs a) {
                     Mc[no][nt] = make_float4(0.f, 0.f, 0.f, 0.f);
                 }
         }
-        if (--g_left == 0) {   // end of tap (i_cp, j_cp)
+        if (!TAP && --g_left == 0) {   // end of tap (i_cp, j_cp); the tap form keeps M for its epilogue
             g_left = groups;
             in_chunk = 0;
             if constexpr (DUMP) gam_cp = 0;
@@ -442,6 +448,25 @@ __global__ __launch_bounds__(64 * NWO * NWT, 2) void k_wino_lds(const LArgs a) {
                     }
             }
         }
+    } else if constexpr (TAP) {
+        const __amdgpu_buffer_rsrc_t rM = __builtin_amdgcn_make_buffer_rsrc(
+            a.Rbuf, 0, (int)(n2 * (unsigned)T_pad * (unsigned)Cout_pad * 4u), kBufFlags);
+#pragma unroll
+        for (int nt = 0; nt < BM; ++nt) {
+            const int tau = (tb0 + BM * wt + nt) * 16 + l16;
+#pragma unroll
+            for (int no = 0; no < BN; ++no) {
+                const int o = (ob0 + BN * wo + no) * 16 + 4 * q;
+                if (tau >= T_pad || o >= Cout_pad) continue;
+                float4 Mv = Mc[no][nt];
+                if constexpr (WIDE)
+                    Mv = make_float4((float)(Mt[no][nt][0] + (double)Mv.x), (float)(Mt[no][nt][1] + (double)Mv.y),
+                                     (float)(Mt[no][nt][2] + (double)Mv.z), (float)(Mt[no][nt][3] + (double)Mv.w));
+                const unsigned off = (((unsigned)tau * n2 + (unsigned)row_i) * (unsigned)Cout_pad + (unsigned)o) * 4u;
+                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, v4f{Mv.x, Mv.y, Mv.z, Mv.w}), rM, off,
+                                                       0, kWriteThrough);
+            }
+        }
     } else {
         const __amdgpu_buffer_rsrc_t rR = __builtin_amdgcn_make_buffer_rsrc(
             a.Rbuf, 0, (int)((unsigned)T_pad * (unsigned)(n * M) * (unsigned)Cout_pad * 4u), kBufFlags);
@@ -465,18 +490,18 @@ __global__ __launch_bounds__(64 * NWO * NWT, 2) void k_wino_lds(const LArgs a) {
     }
 }
 
-template <int M, bool K64, bool CPG1, bool WIDE, bool FULL, bool DUMP, int NWO, int NWT, int BN, int BM, int NS>
+template <int M, bool K64, bool CPG1, bool WIDE, bool FULL, bool DUMP, int NWO, int NWT, int BN, int BM, int NS, bool TAP = false>
 void launch_tile(const LArgs &a0, hipStream_t s) {
     LArgs a = a0;
     constexpr int n = M + 2;
     a.nOBt = (a.Cout_pad + 16 * NWO * BN - 1) / (16 * NWO * BN);
     a.nTBt = (a.T_pad + 16 * NWT * BM - 1) / (16 * NWT * BM);
-    a.total = a.nOBt * a.nTBt * (FULL ? 1 : n);
+    a.total = a.nOBt * a.nTBt * (FULL ? 1 : (TAP ? n * n : n));
     a.per_xcd = (a.total + 7) / 8;
     // neighbours in launch order share the larger operand's tiles: with more weight bytes than
     // activation bytes the tile index runs fastest (the same weight tile for consecutive workgroups)
     a.tb_fastest = (long)a.Cout_pad > (long)a.T_pad ? 1 : 0;
-    hipLaunchKernelGGL((k_wino_lds<M, K64, CPG1, WIDE, FULL, DUMP, NWO, NWT, BN, BM, NS>), dim3((unsigned)a.per_xcd * 8u),
+    hipLaunchKernelGGL((k_wino_lds<M, K64, CPG1, WIDE, FULL, DUMP, NWO, NWT, BN, BM, NS, TAP>), dim3((unsigned)a.per_xcd * 8u),
                        dim3(64 * NWO * NWT), 0, s, a);
 }
 
@@ -498,6 +523,9 @@ void launch_variant(const LArgs &a, hipStream_t s, int variant) {
             break;
         case WQ_K2_LDS_ROW_64x64:
             launch_tile<M, K64, CPG1, WIDE, false, DUMP, 2, 2, 2, 2, 6>(a, s);   // 3 workgroups' rings per CU
+            break;
+        case WQ_K2_LDS_TAP_64x64:   // 4 stages: four workgroups' rings per CU
+            launch_tile<M, K64, CPG1, WIDE, false, DUMP, 2, 2, 2, 2, 4, true>(a, s);
             break;
         default:   // WQ_K2_LDS_ROW_32x64
             launch_tile<M, K64, CPG1, WIDE, false, DUMP, 4, 1, 1, 2, 8>(a, s);

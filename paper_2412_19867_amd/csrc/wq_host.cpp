@@ -165,7 +165,8 @@ bool variant_applicable(const wq_plan *p, int v) {
         case WQ_K2_LDS_FULL_64x64: return p->m == 4;   // 16 waves of F(6,3) state do not fit the registers
         case WQ_K2_LDS_FULL_32x64:
         case WQ_K2_LDS_ROW_64x64:
-        case WQ_K2_LDS_ROW_32x64: return p->m != 2;    // instantiated for F(4,3) and F(6,3)
+        case WQ_K2_LDS_ROW_32x64:
+        case WQ_K2_LDS_TAP_64x64: return p->m != 2;    // instantiated for F(4,3) and F(6,3)
         default: return false;
     }
 }
@@ -190,6 +191,9 @@ int default_k2_variant(const wq_plan *p) {
             return WQ_K2_GEMM_128x128;
         // 32-tile workgroups when 64-tile ones would leave half a tile row of blocks empty
         if ((p->T_pad % 64) == 32 && p->T_pad <= 160) return WQ_K2_GEMM_32x128;
+        // two to eight 64-tile blocks: the same tiling with the operands staged in LDS measures ahead
+        if (p->T_pad >= 128 && p->T_pad <= 512 && p->g < 128 && variant_applicable(p, WQ_K2_LDS_TAP_64x64))
+            return WQ_K2_LDS_TAP_64x64;
         return WQ_K2_GEMM_64x64;
     }
     if (!variant_applicable(p, WQ_K2_FUSED_32x16)) return WQ_K2_FUSED_16x16;
@@ -205,7 +209,8 @@ int default_k2_variant(const wq_plan *p) {
 void publish_choices(wq_plan *p) {
     p->lay.k2_variant = p->k2_variant;
     p->lay.k1_rows = p->k1_rows;
-    p->lay.k2_kernels = (wq_is_gemm_variant(p->k2_variant) || wq_is_lds_row_variant(p->k2_variant)) ? 2 : 1;
+    p->lay.k2_kernels = (wq_is_gemm_variant(p->k2_variant) || wq_is_lds_row_variant(p->k2_variant) ||
+                         wq_is_lds_tap_variant(p->k2_variant)) ? 2 : 1;
 }
 
 struct Blob {
@@ -348,7 +353,7 @@ wq_status_t wq_plan_tune(wq_plan_t *plan, int k1_rows, int k2_variant) {
         case WQ_K2_FUSED_16x16: case WQ_K2_FUSED_KSPLIT: case WQ_K2_FUSED_32x16: case WQ_K2_FUSED_32x32:
         case WQ_K2_GEMM_64x64: case WQ_K2_GEMM_32x128: case WQ_K2_GEMM_128x128:
         case WQ_K2_LDS_FULL_64x64: case WQ_K2_LDS_FULL_32x64:
-        case WQ_K2_LDS_ROW_64x64: case WQ_K2_LDS_ROW_32x64: break;
+        case WQ_K2_LDS_ROW_64x64: case WQ_K2_LDS_ROW_32x64: case WQ_K2_LDS_TAP_64x64: break;
         default: return WQ_ERR_INVALID_ARG;
     }
     if (k1_rows != 0 && !k1_rows_ok(plan, k1_rows)) return WQ_ERR_UNSUPPORTED;

@@ -78,7 +78,7 @@ def test_plan_tune_is_validated_on_the_host(wq):
             continue
         p.tune(0, name)
         assert p.layout.k2_variant == code
-        assert p.layout.k2_kernels == (2 if name.startswith(("gemm", "lds_row")) else 1)
+        assert p.layout.k2_kernels == (2 if name.startswith(("gemm", "lds_row", "lds_tap")) else 1)
     with pytest.raises(wq.WqError) as e:
         p.tune(0, "gemm_128x128")        # groups of 64: that instance needs 128 and more
     assert e.value.status == 2

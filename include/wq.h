@@ -127,9 +127,10 @@ wq_status_t wq_plan_layout(const wq_plan_t *plan, wq_layout_t *out);
  *   LDS_ROW_*  one workgroup per (tile block, channel block, tap row): the same staged
  *             contraction over the n taps of a row folded into row sums of Y A, which go
  *             to the workspace; a small second kernel applies A^T and the bias;
- *   LDS_TAP_64x64  one workgroup per (tile block, channel block, tap): the staged contraction of
+ *   LDS_TAP_*  one workgroup per (tile block, channel block, tap): the staged contraction of
  *             one tap, its fp32 products M written to the workspace like GEMM_* does, then the
- *             same output-transform kernel. */
+ *             same output-transform kernel (128x128: 64x64 per wave, reductions of at most 16
+ *             groups). */
 typedef enum {
     WQ_K2_AUTO = -1,
     WQ_K2_FUSED_16x16 = 0,
@@ -143,7 +144,8 @@ typedef enum {
     WQ_K2_LDS_FULL_32x64 = 21,
     WQ_K2_LDS_ROW_64x64 = 30,
     WQ_K2_LDS_ROW_32x64 = 31,
-    WQ_K2_LDS_TAP_64x64 = 40
+    WQ_K2_LDS_TAP_64x64 = 40,
+    WQ_K2_LDS_TAP_128x128 = 41
 } wq_k2_variant_t;
 
 /* Tuning overrides (tests and sweeps; results stay within the documented

@@ -88,6 +88,7 @@ hipError_t wq_launch_contract_lds(const wq_plan *p, hipStream_t s, const int8_t 
     a.log2g = 0;
     while ((1 << a.log2g) < p->g) ++a.log2g;
     a.nOBt = a.nTBt = a.total = a.per_xcd = a.tb_fastest = 0;
+    a.plain_stores = (long long)p->n * p->n * p->T_pad * p->Cout_pad * 4 > (128LL << 20);
     if (p->m != 4 && p->m != 6) return hipErrorInvalidValue;   // the plan never picks these variants for F(2,3)
     hipError_t e = hipSuccess;
     if (parts & 1) {

@@ -68,6 +68,7 @@ struct LArgs {
     // workgroup tiles along channels and tiles, the number of workgroups, the share of each XCD,
     // and which of the two tile indices runs fastest (set by the launcher)
     int nOBt, nTBt, total, per_xcd, tb_fastest;
+    int plain_stores;   // TAP: M is far larger than the caches - write it back lazily instead of through
 };
 
 #define WQ_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
@@ -111,13 +112,14 @@ __global__ __launch_bounds__(64 * NWO * NWT, 2) void k_wino_lds(const LArgs a) {
     constexpr int LW = (NWL + NW - 1) / NW;            // of which each wave issues this many
     constexpr int OPB = LW * NW * 1024;                // operand bytes per stage (rounded up to that)
     constexpr int NSW = OBW * 16, NSX = TBW * 16;      // scales per stage
-    // a stage: operands, 64 weight scales, 64 activation scales, 64 words nobody reads (the
-    // scale load of the waves that have none to fetch)
-    constexpr int STAGE = OPB + 768;
+    constexpr int NLW = (NSW + 63) / 64, NLX = (NSX + 63) / 64;   // wave-wide scale loads per stage
+    // a stage: operands, the weight scales, the activation scales (64 words per wave-wide load),
+    // 64 words nobody reads (the scale load of the waves that have none to fetch)
+    constexpr int STAGE = OPB + (NLW + NLX + 1) * 256;
     constexpr int D = NS - 2;                          // steps in flight
     constexpr int LPS = LW + 1;                        // loads per wave and step
     static_assert(NS >= 4 && NS % 2 == 0, "ring size (the operand register sets alternate with the step's parity)");
-    static_assert(NW >= 2 && NSW <= 64 && NSX <= 64, "wave 0 fetches the weight scales, wave 1 the activation scales");
+    static_assert(NLW + NLX <= NW, "one scale load per wave and step: the first waves fetch the weight scales, the next the activation scales");
     static_assert(K64 || OBW % 2 == 0, "a wave's 64 chunks must not straddle weights and activations");
     static_assert(D * LPS < 64, "the wait counts loads");
     __shared__ __attribute__((aligned(16))) char ring[NS * STAGE];
@@ -177,20 +179,23 @@ __global__ __launch_bounds__(64 * NWO * NWT, 2) void k_wino_lds(const LArgs a) {
         jumpOp[u] = plane - (unsigned)cps * BLK;
         lastOp[u] = t_last * plane + (unsigned)(cps - 1) * BLK;
     }
-    // the scales of a group: wave 0 the weight scales, wave 1 the activation scales, one per lane;
-    // the other waves issue the same load past the end of the buffer (every wave has the same
-    // number of loads in flight per step, which the counted wait relies on)
+    // the scales of a group, one per lane: waves [0, NLW) fetch 64 weight scales each, waves
+    // [NLW, NLW + NLX) 64 activation scales each (4 tile blocks of 16); the other waves issue the
+    // same load past the end of the buffer (every wave has the same number of loads in flight per
+    // step, which the counted wait relies on)
+    const bool is_sw = w < NLW, is_sx = !is_sw && w < NLW + NLX;
     unsigned vsc = kInvalid;
-    if (w == 0 && lane < NSW && ob0 * 16 + lane < Cout_pad) vsc = (unsigned)(ob0 * 16 + lane) * 4u;
-    if (w == 1 && lane < NSX && (tb0 + (lane >> 4)) * 16 < T_pad)
-        vsc = (unsigned)((tb0 + (lane >> 4)) * groups * 64 + (lane & 15) * 4);
-    const int sc_slot = OPB + (w == 0 ? 0 : (w == 1 ? 256 : 512));
-    const __amdgpu_buffer_rsrc_t rSc = w == 0 ? rSW : rSX;
-    const unsigned stepSc = w == 0 ? stepSW : 64u;                                  // per group
-    const unsigned jumpSc = w == 0 ? 0u : planeSX - (unsigned)groups * 64u;         // per tap
-    unsigned oSc = w == 0 ? t_first * (unsigned)groups * stepSW : t_first * planeSX;
-    const unsigned lastSc = oSc + (w == 0 ? (unsigned)NTAPS * groups * stepSW - stepSW
-                                          : (unsigned)(NTAPS - 1) * planeSX + (unsigned)(groups - 1) * 64u);
+    if (is_sw && 64 * w + lane < NSW && ob0 * 16 + 64 * w + lane < Cout_pad)
+        vsc = (unsigned)(ob0 * 16 + 64 * w + lane) * 4u;
+    if (is_sx && 64 * (w - NLW) + lane < NSX && (tb0 + 4 * (w - NLW) + (lane >> 4)) * 16 < T_pad)
+        vsc = (unsigned)((tb0 + 4 * (w - NLW) + (lane >> 4)) * groups * 64 + (lane & 15) * 4);
+    const int sc_slot = OPB + 256 * min(w, NLW + NLX);
+    const __amdgpu_buffer_rsrc_t rSc = is_sw ? rSW : rSX;
+    const unsigned stepSc = is_sw ? stepSW : 64u;                                  // per group
+    const unsigned jumpSc = is_sw ? 0u : planeSX - (unsigned)groups * 64u;         // per tap
+    unsigned oSc = is_sw ? t_first * (unsigned)groups * stepSW : t_first * planeSX;
+    const unsigned lastSc = oSc + (is_sw ? (unsigned)NTAPS * groups * stepSW - stepSW
+                                         : (unsigned)(NTAPS - 1) * planeSX + (unsigned)(groups - 1) * 64u);
     int k_ld = 0;
 
     auto issue = [&](int stage) {   // request the cursor's step into ring stage `stage` (a constant after unrolling)
@@ -359,7 +364,7 @@ __global__ __launch_bounds__(64 * NWO * NWT, 2) void k_wino_lds(const LArgs a) {
 #pragma unroll
         for (int e = 0; e < BN; ++e) sw[e] = *reinterpret_cast<const v4f *>(&sc[(BN * wo + e) * 16 + 4 * q]);
 #pragma unroll
-        for (int e = 0; e < BM; ++e) sx[e] = sc[64 + (BM * wt + e) * 16 + l16];
+        for (int e = 0; e < BM; ++e) sx[e] = sc[64 * NLW + (BM * wt + e) * 16 + l16];
     };
     auto mfma_blocks = [&](v4i (&ac)[BN][BM], const v4i (&av)[BN], const v4i (&bv)[BM], bool fresh) {
 #pragma unroll
@@ -404,12 +409,17 @@ __global__ __launch_bounds__(64 * NWO * NWT, 2) void k_wino_lds(const LArgs a) {
                 read_scales((v + 1) % NS, swS[u ^ 1], sxS[u ^ 1]);
                 finish_group(acc, swS[u], sxS[u]);
             } else {
-                const int s = sb + v;
-                const bool first = (s & cpg_mask) == 0, last = ((s + 1) & cpg_mask) == 0;
-                mfma_blocks(acc, avS[u], bvS[u], first);
+                // several K-steps per group: the MFMAs accumulate; the sums are cleared when the
+                // group is done (a select on every step would cost one instruction per register)
+                const bool last = ((sb + v + 1) & cpg_mask) == 0;
+                mfma_blocks(acc, avS[u], bvS[u], false);
                 if (last) {
                     read_scales(v, swS[0], sxS[0]);
                     finish_group(acc, swS[0], sxS[0]);
+#pragma unroll
+                    for (int no = 0; no < BN; ++no)
+#pragma unroll
+                        for (int nt = 0; nt < BM; ++nt) acc[no][nt] = v4i{0, 0, 0, 0};
                 }
             }
         }
@@ -463,8 +473,9 @@ __global__ __launch_bounds__(64 * NWO * NWT, 2) void k_wino_lds(const LArgs a) {
                     Mv = make_float4((float)(Mt[no][nt][0] + (double)Mv.x), (float)(Mt[no][nt][1] + (double)Mv.y),
                                      (float)(Mt[no][nt][2] + (double)Mv.z), (float)(Mt[no][nt][3] + (double)Mv.w));
                 const unsigned off = (((unsigned)tau * n2 + (unsigned)row_i) * (unsigned)Cout_pad + (unsigned)o) * 4u;
-                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, v4f{Mv.x, Mv.y, Mv.z, Mv.w}), rM, off,
-                                                       0, kWriteThrough);
+                const v4i bits = __builtin_bit_cast(v4i, v4f{Mv.x, Mv.y, Mv.z, Mv.w});
+                if (a.plain_stores) __builtin_amdgcn_raw_buffer_store_b128(bits, rM, off, 0, 0);
+                else __builtin_amdgcn_raw_buffer_store_b128(bits, rM, off, 0, kWriteThrough);
             }
         }
     } else {
@@ -525,6 +536,13 @@ void launch_variant(const LArgs &a, hipStream_t s, int variant) {
             launch_tile<M, K64, CPG1, WIDE, false, DUMP, 2, 2, 2, 2, 6>(a, s);   // 3 workgroups' rings per CU
             break;
         case WQ_K2_LDS_TAP_64x64:   // 4 stages: four workgroups' rings per CU
+            launch_tile<M, K64, CPG1, WIDE, false, DUMP, 2, 2, 2, 2, 4, true>(a, s);
+            break;
+        case WQ_K2_LDS_TAP_128x128:   // 64x64 per wave: 16 MFMAs per 8 operand blocks read from LDS
+            if constexpr (!WIDE) {    // (with fp64 chunk totals 16 blocks per wave do not fit the registers)
+                launch_tile<M, K64, CPG1, WIDE, false, DUMP, 2, 2, 4, 4, 4, true>(a, s);
+                break;
+            }
             launch_tile<M, K64, CPG1, WIDE, false, DUMP, 2, 2, 2, 2, 4, true>(a, s);
             break;
         default:   // WQ_K2_LDS_ROW_32x64

@@ -167,6 +167,7 @@ bool variant_applicable(const wq_plan *p, int v) {
         case WQ_K2_LDS_ROW_64x64:
         case WQ_K2_LDS_ROW_32x64:
         case WQ_K2_LDS_TAP_64x64: return p->m != 2;    // instantiated for F(4,3) and F(6,3)
+        case WQ_K2_LDS_TAP_128x128: return p->m != 2 && p->groups <= 16;   // no fp64 chunk totals at this wave tile
         default: return false;
     }
 }
@@ -188,7 +189,7 @@ int default_k2_variant(const wq_plan *p) {
     if (two_kernel) {
         // 128x128 tiles: groups of 128 and more on layers with at least 1024 tiles and 256 channels
         if (p->g >= 128 && p->groups <= 8 && p->T_pad >= 1024 && p->Cout_pad >= 256)
-            return WQ_K2_GEMM_128x128;
+            return variant_applicable(p, WQ_K2_LDS_TAP_128x128) ? WQ_K2_LDS_TAP_128x128 : WQ_K2_GEMM_128x128;
         // 32-tile workgroups when 64-tile ones would leave half a tile row of blocks empty
         if ((p->T_pad % 64) == 32 && p->T_pad <= 160) return WQ_K2_GEMM_32x128;
         // two to eight 64-tile blocks: the same tiling with the operands staged in LDS measures ahead
@@ -353,7 +354,7 @@ wq_status_t wq_plan_tune(wq_plan_t *plan, int k1_rows, int k2_variant) {
         case WQ_K2_FUSED_16x16: case WQ_K2_FUSED_KSPLIT: case WQ_K2_FUSED_32x16: case WQ_K2_FUSED_32x32:
         case WQ_K2_GEMM_64x64: case WQ_K2_GEMM_32x128: case WQ_K2_GEMM_128x128:
         case WQ_K2_LDS_FULL_64x64: case WQ_K2_LDS_FULL_32x64:
-        case WQ_K2_LDS_ROW_64x64: case WQ_K2_LDS_ROW_32x64: case WQ_K2_LDS_TAP_64x64: break;
+        case WQ_K2_LDS_ROW_64x64: case WQ_K2_LDS_ROW_32x64: case WQ_K2_LDS_TAP_64x64: case WQ_K2_LDS_TAP_128x128: break;
         default: return WQ_ERR_INVALID_ARG;
     }
     if (k1_rows != 0 && !k1_rows_ok(plan, k1_rows)) return WQ_ERR_UNSUPPORTED;

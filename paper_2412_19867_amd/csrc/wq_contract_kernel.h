@@ -28,15 +28,11 @@
 
 #include <stdlib.h>
 
+#include "wq_device.h"
 #include "wq_internal.h"
 
 namespace {   // every including file instantiates its own tile size; nothing here is exported
 
-typedef int v4i __attribute__((ext_vector_type(4)));
-typedef int v2i __attribute__((ext_vector_type(2)));
-typedef float v4f __attribute__((ext_vector_type(4)));
-
-constexpr int kBufFlags = 0x00020000;   // raw buffer, 32-bit elements (gfx9 family)
 #ifndef WQ_D_BASE
 #define WQ_D_BASE 4
 #endif

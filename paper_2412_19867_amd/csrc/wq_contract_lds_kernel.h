@@ -43,16 +43,12 @@
 //         (four waves per SIMD), for layers with very few tiles and long reductions.
 #pragma once
 
+#include "wq_device.h"
 #include "wq_internal.h"
 
 namespace {   // every including file instantiates its own tile size; nothing here is exported
 
-typedef int v4i __attribute__((ext_vector_type(4)));
-typedef int v2i __attribute__((ext_vector_type(2)));
-typedef float v4f __attribute__((ext_vector_type(4)));
-constexpr int kBufFlags = 0x00020000;     // raw buffer, 32-bit elements (gfx9 family)
-constexpr unsigned kInvalid = 1u << 31;   // an offset past the end of any buffer (all < 2 GiB): loads 0
-constexpr int kWriteThrough = 17;         // cache policy sc0 sc1 of a store
+constexpr unsigned kInvalid = kPastEnd;
 
 struct LArgs {
     wq_xf xf;

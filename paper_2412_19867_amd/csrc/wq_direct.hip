@@ -20,6 +20,7 @@
 #include <cstring>
 #include <new>
 
+#include "wq_device.h"
 #include "wq_internal.h"
 
 struct wq_direct_plan {
@@ -34,22 +35,7 @@ struct wq_direct_plan {
 
 namespace {
 
-typedef int v4i __attribute__((ext_vector_type(4)));
-typedef int v2i __attribute__((ext_vector_type(2)));
-typedef float v4f __attribute__((ext_vector_type(4)));
-constexpr int kBufFlags = 0x00020000;
-constexpr unsigned kInvalid = 1u << 31;   // an offset past the end of any buffer (all < 2 GiB): loads 0
-
-template <int CTRL>
-__device__ __forceinline__ uint32_t dpp_max(uint32_t v) {
-    return max(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xf, 0xf, true));
-}
-
-__device__ __forceinline__ uint32_t quant_code(float v, float r) {
-    const float p = v * r;             // one rounded product (contraction is off)
-    const float z = p + 12582912.0f;   // 1.5*2^23: the add rounds p to nearest-even integer
-    return __float_as_uint(z) & 0xffu;
-}
+constexpr unsigned kInvalid = kPastEnd;
 
 // ------------------------------------------------------------ activations
 // 8 lanes per (pixel, group); a lane owns CPL = g/8 consecutive channels.

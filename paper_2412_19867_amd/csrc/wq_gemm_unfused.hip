@@ -19,17 +19,12 @@
 #include <cstdlib>
 #include <cstring>
 
+#include "wq_device.h"
 #include "wq_internal.h"
 
 namespace {
 
-typedef int v4i __attribute__((ext_vector_type(4)));
-typedef int v2i __attribute__((ext_vector_type(2)));
-typedef float v4f __attribute__((ext_vector_type(4)));
-constexpr int kBufFlags = 0x00020000;
-// cache policy sc0 sc1 of a store: written through to memory while the kernel runs instead of
-// being flushed from the XCD's L2 when it ends (measured: 3 % of the ResNet layer set's step)
-constexpr int kWriteThrough = 17;
+// (writing M through, see kWriteThrough, measured 3 % of the ResNet layer set's step)
 
 struct GArgs {
     const int8_t *Xq;
@@ -58,7 +53,7 @@ __global__ __launch_bounds__(256, 2) void k_gemm_dequant(const GArgs a) {
     constexpr int WN = TBW == 2 ? 4 : 2, WM = 4 / WN;   // waves along channels / along tiles
     constexpr int BN = OBW / WN, BM = TBW / WM;         // 16x16 blocks per wave along channels / tiles
     constexpr int NSW = OBW * 16, NSX = TBW * 16;       // scales per stage
-    constexpr unsigned kInvalid = 1u << 31;      // an offset past the end of any buffer (all < 2 GiB): loads 0
+    constexpr unsigned kInvalid = kPastEnd;
     __shared__ __attribute__((aligned(16))) char opnd[2][NB * BLK];
     __shared__ __attribute__((aligned(16))) float sc[2][NSW + NSX];   // weight scales, then activation scales
 

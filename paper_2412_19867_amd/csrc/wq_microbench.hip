@@ -5,13 +5,10 @@
 // pair of scales on every group of the reduction, so the int32 sums cannot be carried across
 // groups).  No memory traffic: operands and scales live in registers, so the figure is the
 // ceiling the matrix core and the vector ALU set together, per group size.
+#include "wq_device.h"
 #include "wq_internal.h"
 
 namespace {
-
-typedef int v4i __attribute__((ext_vector_type(4)));
-typedef int v2i __attribute__((ext_vector_type(2)));
-typedef float v4f __attribute__((ext_vector_type(4)));
 
 // MODE 0: MFMA only.  1: dequantization only (on a register that changes every iteration).
 // 2: MFMA, then the dequantization of its result (as written in a straightforward loop).

@@ -27,23 +27,14 @@
 #include <float.h>
 #include <stdlib.h>
 
+#include "wq_device.h"
 #include "wq_internal.h"
 
 namespace {
 
-typedef int v2i __attribute__((ext_vector_type(2)));
-typedef int v4i __attribute__((ext_vector_type(4)));
-constexpr int kBufFlags = 0x00020000;   // raw buffer, 32-bit elements (gfx9 family)
-constexpr unsigned kInvalid = 1u << 30;  // added to an offset to push it past the buffer end
-// cache policy sc0 sc1 of a store: the data is written through to memory while the kernel runs
-// instead of being flushed from the XCD's L2 when it ends (measured: 5-8 % of the input kernel)
-constexpr int kWriteThrough = 17;
-
-template <int CTRL>
-__device__ __forceinline__ uint32_t dpp_max(uint32_t v) {
-    // bound_ctrl with a zero fill lets the compiler fold the move into v_max_u32_dpp
-    return max(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xf, 0xf, true));
-}
+// added to a row or column offset to push the sum past the buffer end (two of them may add up)
+constexpr unsigned kInvalid = 1u << 30;
+// (writing the codes through, see kWriteThrough, measured 5-8 % of the input kernel)
 
 // max over each aligned group of 4 lanes, result in all 4 lanes
 __device__ __forceinline__ uint32_t quad_max(uint32_t v) {
@@ -56,13 +47,6 @@ __device__ __forceinline__ uint32_t quad_max(uint32_t v) {
 // finite results of fused multiply-adds, so the float maximum orders them like their bits.
 __device__ __forceinline__ uint32_t abs_max_bits(float a, float b) {
     return __float_as_uint(__builtin_fmaxf(__builtin_fabsf(a), __builtin_fabsf(b)));
-}
-
-// rint(v*r) as the low byte of a two's-complement code; |v*r| <= 127 + ulp.
-__device__ __forceinline__ uint32_t quant_code(float v, float r) {
-    const float p = v * r;                   // one rounded product (contraction is off)
-    const float z = p + 12582912.0f;         // 1.5*2^23: the add rounds p to nearest-even integer
-    return __float_as_uint(z) & 0xffu;
 }
 
 // Byte offset of a lane's two codes inside one 16-row block of the operand

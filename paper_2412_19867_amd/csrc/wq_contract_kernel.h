@@ -350,7 +350,7 @@ __global__ __launch_bounds__(64 * (M + 2) * KS) void k_contract_output(const Arg
 #pragma unroll
                         for (int aa = 0; aa < M; ++aa)
                             if (aa < hv)   // streaming store: y is not read again by this layer
-                                __builtin_nontemporal_store(Yv[aa] + bias_v[no],
+                                store_y(Yv[aa] + bias_v[no],
                                                             &dst[(size_t)aa * a.W * a.Cout]);
                     }
                 }

@@ -54,11 +54,11 @@ __global__ __launch_bounds__(256) void k_row_finish(const FArgs a) {
         const v4f out = {ox[aa] + bv4.x, oy[aa] + bv4.y, oz[aa] + bv4.z, ow[aa] + bv4.w};
         float *dst = base + (size_t)aa * a.W * a.Cout;
         if (vec) {
-            __builtin_nontemporal_store(out, reinterpret_cast<v4f *>(dst));
+            store_y(out, reinterpret_cast<v4f *>(dst));
         } else {
 #pragma unroll
             for (int r = 0; r < 4; ++r)
-                if (o + r < a.Cout) __builtin_nontemporal_store(out[r], dst + r);
+                if (o + r < a.Cout) store_y(out[r], dst + r);
         }
     }
 }

@@ -445,11 +445,11 @@ __global__ __launch_bounds__(64 * NWO * NWT, 2) void k_wino_lds(const LArgs a) {
                         float *dst = base + ((size_t)aa * a.W + b) * a.Cout + o;
                         const v4f out = {Yv.x + bv4.x, Yv.y + bv4.y, Yv.z + bv4.z, Yv.w + bv4.w};
                         if (vec) {   // streaming store: y is not read again by this layer
-                            __builtin_nontemporal_store(out, reinterpret_cast<v4f *>(dst));
+                            store_y(out, reinterpret_cast<v4f *>(dst));
                         } else {
 #pragma unroll
                             for (int r = 0; r < 4; ++r)
-                                if (o + r < a.Cout) __builtin_nontemporal_store(out[r], dst + r);
+                                if (o + r < a.Cout) store_y(out[r], dst + r);
                         }
                     }
             }

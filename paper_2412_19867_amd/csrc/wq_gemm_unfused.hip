@@ -321,7 +321,7 @@ __global__ __launch_bounds__(64 * M) void k_output_transform(const OArgs a) {
         for (int aa = 0; aa < M; ++aa) {
             const float yv = Yv[aa];
             if (aa < hv)   // streaming store: y is not read again by this layer
-                __builtin_nontemporal_store(yv + bv, &dst[(size_t)aa * a.W * a.Cout]);
+                store_y(yv + bv, &dst[(size_t)aa * a.W * a.Cout]);
         }
     }
 }

@@ -107,8 +107,9 @@ def main():
                     help="launch warmup+steps steps eagerly, print the launch count and exit (for counter "
                          "runs: every dispatch in the process then belongs to a step)")
     ap.add_argument("--k2-variant", default=None,
-                    help="force this kernel variant of stages 2+3 on every layer it applies to (for "
-                         "before/after profiles; the default is the plan's own choice per layer)")
+                    help="force this kernel variant of stages 2+3 on every layer it applies to, or "
+                         "'i:name,j:name' on layers i, j of the set (for before/after profiles; the "
+                         "default is the plan's own choice per layer)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a 256 MiB device-to-device copy three times (known HBM traffic, "
                          "used to calibrate the FETCH_SIZE / WRITE_SIZE counters) and exit")
@@ -138,7 +139,7 @@ def main():
     def build_items(cfg):
         """One entry per convolution launched in a step (a layer with repeat=r gives r chained convs)."""
         items = []
-        for lay in workloads.CONFIGS[cfg]:
+        for li, lay in enumerate(workloads.CONFIGS[cfg]):
             d = workloads.make_layer_data(lay)
             kw = {}
             if d.u_B is not None:
@@ -146,10 +147,14 @@ def main():
                 kw = dict(AT=AT, BT=BT, G=G)
             plan = wq.Plan(lay.N, lay.H, lay.W, lay.Cin, lay.Cout, lay.m, lay.group_size, **kw)
             if args.k2_variant:
-                try:
-                    plan.tune(0, args.k2_variant)
-                except wq.WqError:
-                    pass   # not applicable to this layer: the plan's own choice stays
+                # "name" = every layer, "i:name,j:name" = layers i, j of the set
+                want = dict(v.split(":") for v in args.k2_variant.split(",")) if ":" in args.k2_variant \
+                    else {str(li): args.k2_variant}
+                if str(li) in want:
+                    try:
+                        plan.tune(0, want[str(li)])
+                    except wq.WqError:
+                        pass   # not applicable to this layer: the plan's own choice stays
             x = torch.from_numpy(d.x).cuda()
             w, b = torch.from_numpy(d.w).cuda(), torch.from_numpy(d.bias).cuda()
             for r in range(lay.repeat):

@@ -110,6 +110,9 @@ def main():
                     help="force this kernel variant of stages 2+3 on every layer it applies to, or "
                          "'i:name,j:name' on layers i, j of the set (for before/after profiles; the "
                          "default is the plan's own choice per layer)")
+    ap.add_argument("--integer-transforms", type=int, default=0, choices=(0, 1, 2),
+                    help="run the workload with the fully-integer input and output transforms (1: one "
+                         "scale per transform matrix, 2: per matrix row) instead of the fp32 ones")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a 256 MiB device-to-device copy three times (known HBM traffic, "
                          "used to calibrate the FETCH_SIZE / WRITE_SIZE counters) and exit")
@@ -136,7 +139,7 @@ def main():
 
     side = torch.cuda.Stream()
 
-    def build_items(cfg):
+    def build_items(cfg, integer_mode=0):
         """One entry per convolution launched in a step (a layer with repeat=r gives r chained convs)."""
         items = []
         for li, lay in enumerate(workloads.CONFIGS[cfg]):
@@ -146,6 +149,8 @@ def main():
                 AT, BT, G = wq.scaled_transforms(lay.m, d.u_B, d.u_G)
                 kw = dict(AT=AT, BT=BT, G=G)
             plan = wq.Plan(lay.N, lay.H, lay.W, lay.Cin, lay.Cout, lay.m, lay.group_size, **kw)
+            if integer_mode:
+                plan.set_integer_transforms(integer_mode)
             if args.k2_variant:
                 # "name" = every layer, "i:name,j:name" = layers i, j of the set
                 want = dict(v.split(":") for v in args.k2_variant.split(",")) if ":" in args.k2_variant \
@@ -214,7 +219,7 @@ def main():
         put("eager launches from Python", timed(step, steps, warmup))
         return timings, spread
 
-    items = build_items(args.config)
+    items = build_items(args.config, args.integer_transforms)
     layers = workloads.CONFIGS[args.config]
 
     def step(with_offline=False):
@@ -398,7 +403,7 @@ def main():
     ceiling = dict(step_ceiling_us=round(sum_ceiling, 1), step_us=round(sec * 1e6, 1),
                    frac=round(sum_ceiling / (sec * 1e6), 3))
 
-    direct = linear = others = None
+    direct = linear = others = integer = None
     if not args.no_extras:
         # ---- the paper's runtime comparison point on the same layers: the group-wise quantized
         # standard (direct) convolution, same quantizer and groups, no transforms
@@ -466,6 +471,24 @@ def main():
                 del o_items
                 torch.cuda.empty_cache()
 
+        # ---- the same workload with the fully-integer input and output transforms (the "next" path:
+        # first and third quantized-stage equations), whole-step time
+        if not args.integer_transforms:
+            i_items = build_items(args.config, 1)
+
+            def i_step():
+                for it in i_items:
+                    it["plan"].forward(it["x"], it["blob"], it["ws"], it["y"])
+
+            i_t, _ = time_step(i_step, args.steps, args.warmup)
+            i_sec = min(i_t.values())
+            integer = dict(value=round(direct_ops / i_sec / 1e12, 2), unit="TOPS", ms_per_step=round(i_sec * 1e3, 4),
+                           launch=min(i_t, key=i_t.get), scales="one per transform matrix",
+                           k2_variants=sorted({it["plan"].k2_variant_name for it in i_items}),
+                           fp32_transforms_over_integer=round(i_sec / sec, 3))
+            del i_items
+            torch.cuda.empty_cache()
+
     cpu_baseline = None
     if not args.no_cpu_baseline and args.config != 6:
         import oracle
@@ -518,12 +541,14 @@ def main():
                     batch=layers[0].N, convs_per_step=n_convs,
                     resident_mb=round(footprint / 1e6, 1)),
         roofline=roofline, ceiling=ceiling, cpu_baseline=cpu_baseline, direct_conv_same_layers=direct,
-        quantized_linear_layer=linear, other_configs=others,
+        quantized_linear_layer=linear, other_configs=others, integer_transforms=integer,
         with_offline_stage=dict(value=round(direct_ops / sec_off / 1e12, 2), unit="TOPS",
                                 ms_per_step=round(sec_off * 1e3, 4)),
         layers=per_layer)
     if args.k2_variant:
         out["config"]["k2_variant_forced"] = args.k2_variant
+    if args.integer_transforms:
+        out["config"]["integer_transforms"] = args.integer_transforms
     print(json.dumps(out))
 
 

@@ -158,6 +158,25 @@ typedef enum {
  * plan's shape, group size or matrices -> UNSUPPORTED (the plan is unchanged). */
 wq_status_t wq_plan_tune(wq_plan_t *plan, int k1_rows, int k2_variant);
 
+/* Fully-integer input and output transforms (first and third quantized-stage
+ * equations of Section "Learnable Winograd transform scales"; the Hadamard
+ * stage between them is the one wq_conv_forward always runs):
+ *   X~ = s_B s_B s_x  Q(B^T/s_B) Q(d/s_x) Q(B/s_B),   y = s_A s_A s_Y  Q(A^T/s_A) Q(Y/s_Y) Q(A/s_A) + bias.
+ * mode 0: off (fp32 transforms, the default); 1: one scale per transform matrix
+ * (abs-max/127); 2: one scale per matrix row.  The plan's fp32 B^T and A^T are
+ * quantized to int8 on the host; s_x is dynamic, one per (tile, group of
+ * group_size input channels) over the n x n x group_size patch; s_Y is dynamic,
+ * one per (tile, output channel) over its n x n Winograd-domain values; the
+ * integer products are exact; scales, the scaled products and the bias add are
+ * evaluated in fp64 and rounded once to fp32 (X~ before the group quantizer of
+ * stage 1, y at the store).  The paper leaves these granularities open; this is
+ * the reading the CPU reference of the tests implements.  Stages 2+3 then run in
+ * a variant that writes the Winograd-domain products to the workspace (GEMM_* or
+ * LDS_TAP_*); wq_plan_tune refuses the others with WQ_ERR_UNSUPPORTED while the
+ * mode is on.  Host call, no device work; call it before wq_weight_prepare or
+ * after, the weight blob does not depend on it. */
+wq_status_t wq_plan_set_integer_transforms(wq_plan_t *plan, int mode);
+
 /* Offline stage (W = G w G^T, then group-wise quantization along Cin):
  * reads w_dev [Cout][Cin][3][3] fp32 and bias_dev [Cout] fp32 (NULL = zero
  * bias) and fills weight_blob_dev (blob_bytes, 256-byte aligned). */

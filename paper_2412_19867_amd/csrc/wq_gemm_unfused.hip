@@ -326,6 +326,69 @@ __global__ __launch_bounds__(64 * M) void k_output_transform(const OArgs a) {
     }
 }
 
+// Third quantized-stage equation of Section "Learnable Winograd transform scales":
+//     y = s_A[a] s_A[b] s_Y  (Q_A Q(Y / s_Y) Q_A^T)[a][b] + bias
+// with the int8 matrix Q_A = Q(A^T / s_A) from the plan and one dynamic scale s_Y = abs-max / 127
+// per (tile, output channel) over its n x n Winograd-domain values; the integer product is exact,
+// scales and bias in fp64, one rounding to fp32 at the store.  One thread per (tile, channel):
+// 4 tiles x 64 channels per workgroup, M [tile][tap][Cout_pad] read straight from the workspace
+// (a wave's 64 lanes read 256 contiguous bytes per tap).
+struct OIArgs {
+    wq_xi xi;
+    const float *Mbuf;
+    const float *bias;
+    float *y;
+    int H, W, Cout, TH, TW, T, T_pad, Cout_pad;
+};
+
+template <int M>
+__global__ __launch_bounds__(256) void k_output_transform_int(const OIArgs a) {
+    constexpr int n = M + 2, n2 = n * n;
+    const int tid = threadIdx.x, ol = tid & 63;
+    const int tau = blockIdx.x * 4 + (tid >> 6), o = blockIdx.y * 64 + ol;
+    if (tau >= a.T || o >= a.Cout) return;
+    const float *src = a.Mbuf + (size_t)tau * n2 * a.Cout_pad + o;
+    float Yv[n2];
+    float am = 0.f;
+#pragma unroll
+    for (int t = 0; t < n2; ++t) {
+        Yv[t] = src[(size_t)t * a.Cout_pad];
+        am = __builtin_fmaxf(am, __builtin_fabsf(Yv[t]));
+    }
+    const double a_y = (double)am;
+    const double s_y = a_y > 0.0 ? a_y / 127.0 : 0.0, r_y = a_y > 0.0 ? 127.0 / a_y : 0.0;
+    int q[n][n];
+#pragma unroll
+    for (int i = 0; i < n; ++i)
+#pragma unroll
+        for (int j = 0; j < n; ++j)
+            q[i][j] = (int)fmin(127.0, fmax(-127.0, rint((double)Yv[i * n + j] * r_y)));
+    int u[M][n];   // Q_A q
+#pragma unroll
+    for (int aa = 0; aa < M; ++aa)
+#pragma unroll
+        for (int j = 0; j < n; ++j) {
+            int acc = 0;
+#pragma unroll
+            for (int i = 0; i < n; ++i) acc += a.xi.QA[aa * n + i] * q[i][j];
+            u[aa][j] = acc;
+        }
+    const int tw = tau % a.TW, th = (tau / a.TW) % a.TH, bb = tau / (a.TW * a.TH);
+    const int hv = min(M, a.H - th * M), wv = min(M, a.W - tw * M);
+    const double bv = (double)a.bias[o];
+    float *base = a.y + ((size_t)(bb * a.H + th * M) * a.W + tw * M) * a.Cout + o;
+#pragma unroll
+    for (int aa = 0; aa < M; ++aa)
+#pragma unroll
+        for (int b = 0; b < M; ++b) {
+            int acc = 0;
+#pragma unroll
+            for (int j = 0; j < n; ++j) acc += u[aa][j] * a.xi.QA[b * n + j];
+            const double v = (a.xi.sAA[aa * M + b] * s_y) * (double)acc + bv;
+            if (aa < hv && b < wv) store_y((float)v, base + ((size_t)aa * a.W + b) * a.Cout);
+        }
+}
+
 // plain, or (debug entry point) the same kernel with the stores of the int32 sums compiled in
 template <bool K64, bool CPG1, bool WIDE, int TBW>
 void launch_one(dim3 grid, hipStream_t s, const GArgs &g) {
@@ -403,6 +466,19 @@ hipError_t wq_launch_contract_unfused(const wq_plan *p, hipStream_t s, const int
     o.xf = p->xf; o.Mbuf = Mbuf; o.bias = bias; o.y = y;
     o.H = p->H; o.W = p->W; o.Cout = p->Cout; o.TH = p->TH; o.TW = p->TW; o.T = p->T;
     o.T_pad = p->T_pad; o.Cout_pad = p->Cout_pad;
+    if (p->integer_transforms) {
+        OIArgs oi;
+        oi.xi = p->xi; oi.Mbuf = Mbuf; oi.bias = bias; oi.y = y;
+        oi.H = p->H; oi.W = p->W; oi.Cout = p->Cout; oi.TH = p->TH; oi.TW = p->TW; oi.T = p->T;
+        oi.T_pad = p->T_pad; oi.Cout_pad = p->Cout_pad;
+        const dim3 igrid((p->T + 3) / 4, (p->Cout + 63) / 64);
+        switch (p->m) {
+            case 2: hipLaunchKernelGGL((k_output_transform_int<2>), igrid, dim3(256), 0, s, oi); break;
+            case 4: hipLaunchKernelGGL((k_output_transform_int<4>), igrid, dim3(256), 0, s, oi); break;
+            default: hipLaunchKernelGGL((k_output_transform_int<6>), igrid, dim3(256), 0, s, oi); break;
+        }
+        return hipGetLastError();
+    }
     const dim3 ogrid(p->T, (p->Cout + 63) / 64);   // tiles along x: y holds 65535 at most
     switch (p->m) {
         case 2: launch_out<2>(o, ogrid, s, p->sparse_at); break;

@@ -153,6 +153,9 @@ bool k1_rows_ok(const wq_plan *p, int rows) {
 }
 
 bool variant_applicable(const wq_plan *p, int v) {
+    // the integer output transform quantizes whole n x n tiles of the Winograd-domain result: only
+    // the forms that write it to the workspace can feed it
+    if (p->integer_transforms && !wq_is_gemm_variant(v) && !wq_is_lds_tap_variant(v)) return false;
     const bool fast_fused_ok = p->sparse_at && p->m != 2 && p->g <= 64;   // instantiated for one K-step per group
     switch (v) {
         case WQ_K2_FUSED_16x16: return true;
@@ -173,6 +176,10 @@ bool variant_applicable(const wq_plan *p, int v) {
 }
 
 int default_k2_variant(const wq_plan *p) {
+    if (p->integer_transforms) {
+        if (p->T_pad <= 32 || ((p->T_pad % 64) == 32 && p->T_pad <= 160)) return WQ_K2_GEMM_32x128;
+        return (p->g < 128 && p->m != 2) ? WQ_K2_LDS_TAP_64x64 : WQ_K2_GEMM_64x64;
+    }
     // The row form with operand tiles shared through LDS: measured ahead of the others where its
     // workgroups (64 tiles x 64 channels x one tap row) fill the GPU once at two to three per CU
     // and each of them walks a reduction long enough to pay for the second kernel.
@@ -298,6 +305,8 @@ wq_status_t wq_plan_create(wq_plan_t **out, int N, int H, int W, int Cin, int Co
     p->kstep = group_size == 32 ? 32 : 64;
     p->wbits = 8;
     p->prepared.store(0);
+    p->integer_transforms = 0;
+    std::memset(&p->xi, 0, sizeof(p->xi));
     std::memset(&p->xf, 0, sizeof(p->xf));
     if (all) {
         std::memcpy(p->xf.BT, BT, sizeof(float) * n * n);
@@ -358,9 +367,52 @@ wq_status_t wq_plan_tune(wq_plan_t *plan, int k1_rows, int k2_variant) {
         default: return WQ_ERR_INVALID_ARG;
     }
     if (k1_rows != 0 && !k1_rows_ok(plan, k1_rows)) return WQ_ERR_UNSUPPORTED;
+    if (plan->integer_transforms && k1_rows != 0 && k1_rows != plan->n) return WQ_ERR_UNSUPPORTED;
     if (k2_variant != WQ_K2_AUTO && !variant_applicable(plan, k2_variant)) return WQ_ERR_UNSUPPORTED;
-    plan->k1_rows = k1_rows ? k1_rows : default_k1_rows(plan);
+    plan->k1_rows = k1_rows ? k1_rows : (plan->integer_transforms ? plan->n : default_k1_rows(plan));
     plan->k2_variant = k2_variant != WQ_K2_AUTO ? k2_variant : default_k2_variant(plan);
+    publish_choices(plan);
+    return WQ_OK;
+}
+
+// Q(M / s), s = abs-max / 127, over a whole matrix or per row; in double on the host.
+static void quantize_matrix(const float *Mx, int rows, int cols, int stride, bool per_row, int *Q, double *s) {
+    double a_all = 0.0;
+    for (int r = 0; r < rows; ++r)
+        for (int c = 0; c < cols; ++c) a_all = std::fmax(a_all, std::fabs((double)Mx[r * stride + c]));
+    for (int r = 0; r < rows; ++r) {
+        double a = a_all;
+        if (per_row) {
+            a = 0.0;
+            for (int c = 0; c < cols; ++c) a = std::fmax(a, std::fabs((double)Mx[r * stride + c]));
+        }
+        s[r] = a > 0.0 ? a / 127.0 : 0.0;
+        const double rcp = a > 0.0 ? 127.0 / a : 0.0;
+        for (int c = 0; c < cols; ++c) {
+            double q = std::nearbyint((double)Mx[r * stride + c] * rcp);   // round half to even
+            q = std::fmin(127.0, std::fmax(-127.0, q));
+            Q[r * stride + c] = (int)q;
+        }
+    }
+}
+
+wq_status_t wq_plan_set_integer_transforms(wq_plan_t *plan, int mode) {
+    if (!plan || mode < 0 || mode > 2) return WQ_ERR_INVALID_ARG;
+    plan->integer_transforms = mode;
+    if (mode) {
+        const int n = plan->n, m = plan->m;
+        double sB[8], sA[8];
+        quantize_matrix(plan->xf.BT, n, n, n, mode == 2, plan->xi.QB, sB);
+        quantize_matrix(plan->xf.AT, m, n, n, mode == 2, plan->xi.QA, sA);
+        for (int i = 0; i < n; ++i)
+            for (int j = 0; j < n; ++j) plan->xi.sBB[i * n + j] = sB[i] * sB[j];
+        for (int a = 0; a < m; ++a)
+            for (int b = 0; b < m; ++b) plan->xi.sAA[a * m + b] = sA[a] * sA[b];
+        plan->k1_rows = n;   // the patch scale needs the whole patch in one workgroup
+    } else {
+        plan->k1_rows = default_k1_rows(plan);
+    }
+    plan->k2_variant = default_k2_variant(plan);
     publish_choices(plan);
     return WQ_OK;
 }

@@ -20,6 +20,17 @@ struct wq_xf {
     float ATr[4];
 };
 
+// The int8 forms of B^T and A^T for the fully-integer transforms (first and third
+// quantized-stage equations of Section "Learnable Winograd transform scales"): codes
+// Q(M / s) with s = abs-max / 127 per matrix (or per row), and the products of the two scales
+// that stand outside an integer product, sBB[i][j] = s_B[i] s_B[j], sAA[a][b] = s_A[a] s_A[b].
+struct wq_xi {
+    int QB[64];      // n x n, row stride n
+    int QA[48];      // m x n, row stride n
+    double sBB[64];  // n x n
+    double sAA[36];  // m x m, row stride m
+};
+
 struct wq_plan {
     int N, H, W, Cin, Cout, m, n, g, groups;
     int TH, TW, T, T_pad, Cout_pad;
@@ -35,6 +46,10 @@ struct wq_plan {
     // the kernel instance of stages 2+3 (a wq_k2_variant_t) and the tap rows per workgroup of the
     // input kernel, picked from the shape when the plan is made (wq_plan_tune overrides them)
     int k2_variant, k1_rows;
+    // 0: fp32 transforms (the path of the second quantized-stage equation alone); 1 / 2: integer
+    // input and output transforms with one scale per transform matrix / per matrix row
+    int integer_transforms;
+    wq_xi xi;
     wq_layout_t lay;
     std::atomic<int> prepared;
 };

@@ -298,6 +298,132 @@ __global__ __launch_bounds__(256) void k_input_transform(wq_xf xf, const float *
 #undef WQ_BODY
 }
 
+// ------------------------------------------- stage 1 with the integer transform
+// First quantized-stage equation of Section "Learnable Winograd transform scales":
+//     X~ = s_B[i] s_B[j] s_x  (Q_B Q(d / s_x) Q_B^T)[i][j]
+// with the int8 matrix Q_B = Q(B^T / s_B) from the plan, one dynamic scale s_x = abs-max / 127 per
+// (tile, group) over the group's n x n x g patch values, the integer product exact in int32
+// (|.| <= n^2 127^3 < 2^31), and the scales applied in fp64 and rounded once to fp32; the result
+// then takes the same group quantizer as the fp32 transform's.  Same thread mapping as
+// k_input_transform with all n tap rows in one workgroup: a row of 16 lanes owns (tile, 32
+// channels), a lane 2 channels, the k = g/32 rows of a group sit side by side.
+template <int M>
+__global__ __launch_bounds__(256) void k_input_transform_int(wq_xi xi, const float *__restrict__ x,
+                                                             int8_t *__restrict__ Xq,
+                                                             float *__restrict__ sX, int H, int W,
+                                                             int Cin, int TH, int TW, int T, int T_pad,
+                                                             int log2k, int kstep_log2,
+                                                             unsigned x_bytes, int total, int per_xcd) {
+    constexpr int n = M + 2, NT = n * n;
+    const int bid = (int)(blockIdx.x & 7u) * per_xcd + (int)(blockIdx.x >> 3);
+    if (bid >= total) return;   // the whole workgroup leaves, before any barrier
+    __shared__ float r_s[NT][16];
+    __shared__ __attribute__((aligned(16))) char codes_s[NT * kTapStride];
+    __shared__ uint32_t patch_s[16][4];
+    uint4 (*amax_s)[16] = reinterpret_cast<uint4 (*)[16]>(codes_s);
+
+    const int tid = threadIdx.x, row = tid >> 4, l16 = tid & 15;
+    const int k = 1 << log2k;
+    const int CC = Cin >> 5, groups = CC >> log2k;
+    const int rb = bid / CC, rem = bid % CC;
+    const int sub = rem / groups, gam = rem % groups;
+    const int row16 = sub * (16 >> log2k) + (row >> log2k);
+    const int chunk = gam * k + (row & (k - 1));
+    const int tau = rb * 16 + row16;
+    const bool tile_ok = tau < T;
+    const int tw = tau % TW, th = (tau / TW) % TH, b = tau / (TW * TH);
+    const int h0 = th * M - 1, w0 = tw * M - 1;
+    const __amdgpu_buffer_rsrc_t rx =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(x), 0, (int)x_bytes, kBufFlags);
+    unsigned roff[n], coff[n];
+#pragma unroll
+    for (int e = 0; e < n; ++e) {
+        const int hh = h0 + e, ww = w0 + e;
+        roff[e] = (tile_ok && hh >= 0 && hh < H) ? (unsigned)((b * H + hh) * W) * (unsigned)Cin * 4u
+                                                 : kInvalid;
+        coff[e] = (ww >= 0 && ww < W) ? (unsigned)(ww * Cin + chunk * 32 + l16 * 2) * 4u : kInvalid;
+    }
+    // the lane's two patches and the abs-max of the group's patch values
+    float2 d[n][n];
+    uint32_t pm = 0;
+#pragma unroll
+    for (int kk = 0; kk < n; ++kk)
+#pragma unroll
+        for (int j = 0; j < n; ++j) {
+            const v2i v = __builtin_amdgcn_raw_buffer_load_b64(rx, roff[kk] + coff[j], 0, 0);
+            d[kk][j] = make_float2(__int_as_float(v.x), __int_as_float(v.y));
+            pm = max(pm, abs_max_bits(d[kk][j].x, d[kk][j].y));
+        }
+    pm = quad_max(pm);
+    patch_s[row][l16 >> 2] = pm;   // the four lanes of a quad store the same word
+    __syncthreads();
+    uint32_t am_bits = 0;
+    {
+        const int r0 = row & ~(k - 1);
+        for (int q = 0; q < k; ++q)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) am_bits = max(am_bits, patch_s[r0 + q][j]);
+    }
+    const double a_x = (double)__uint_as_float(am_bits);
+    const double s_x = a_x > 0.0 ? a_x / 127.0 : 0.0, r_x = a_x > 0.0 ? 127.0 / a_x : 0.0;
+
+    float2 X[NT];
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+        int q[n][n];
+#pragma unroll
+        for (int kk = 0; kk < n; ++kk)
+#pragma unroll
+            for (int j = 0; j < n; ++j) {
+                const double v = (double)(c ? d[kk][j].y : d[kk][j].x) * r_x;
+                q[kk][j] = (int)fmin(127.0, fmax(-127.0, rint(v)));
+            }
+        int t1[n][n];   // Q_B q
+#pragma unroll
+        for (int i = 0; i < n; ++i)
+#pragma unroll
+            for (int j = 0; j < n; ++j) {
+                int acc = 0;
+#pragma unroll
+                for (int kk = 0; kk < n; ++kk) acc += xi.QB[i * n + kk] * q[kk][j];
+                t1[i][j] = acc;
+            }
+#pragma unroll
+        for (int i = 0; i < n; ++i)
+#pragma unroll
+            for (int j = 0; j < n; ++j) {
+                int acc = 0;
+#pragma unroll
+                for (int l = 0; l < n; ++l) acc += t1[i][l] * xi.QB[j * n + l];
+                const float v = (float)((xi.sBB[i * n + j] * s_x) * (double)acc);
+                if (c) X[i * n + j].y = v; else X[i * n + j].x = v;
+            }
+    }
+    __syncthreads();   // patch_s is read; amax_s (below) shares nothing with it, r_s neither
+    // abs-max of each tap over the row's 32 channels, as in the fp32 kernel
+#pragma unroll
+    for (int i = 0; i < n; ++i) {
+        uint32_t am[n];
+#pragma unroll
+        for (int j = 0; j < n; ++j) am[j] = quad_max(abs_max_bits(X[i * n + j].x, X[i * n + j].y));
+        uint32_t *dst = reinterpret_cast<uint32_t *>(&amax_s[i * n][row]) + (l16 >> 2);
+#pragma unroll
+        for (int j = 0; j < n; ++j) dst[j * 64] = am[j];
+    }
+    const int RB = T_pad >> 4;
+    const __amdgpu_buffer_rsrc_t rq = __builtin_amdgcn_make_buffer_rsrc(
+        Xq, 0, (int)((unsigned)(n * n) * (unsigned)T_pad * (unsigned)Cin), kBufFlags);
+    const CodePlace place =
+        code_place(tid, kstep_log2, (unsigned)rb * 16u * (unsigned)Cin, [&](int r, int &cc, int &r16) {
+            cc = gam * k + (r & (k - 1));
+            r16 = sub * (16 >> log2k) + (r >> log2k);
+        });
+    const long scale_base = ((long)rb * groups + gam) * 16 + sub * (16 >> log2k);
+    quantize_and_store<NT>(X, amax_s, r_s, codes_s, log2k, 0, rq, place,
+                           (unsigned)T_pad * (unsigned)Cin, sX, scale_base,
+                           (long)RB * groups * 16, 16);
+}
+
 // ----------------------------------------------------------- offline stage
 template <int M, bool SPARSE, bool W4 = false>
 __global__ __launch_bounds__(256) void k_weight_transform(wq_xf xf, const float *__restrict__ w,
@@ -446,6 +572,14 @@ hipError_t launch_input_rows(const wq_plan *p, hipStream_t s, const float *x, in
 template <int M>
 hipError_t launch_input_m(const wq_plan *p, hipStream_t s, const float *x, int8_t *Xq, float *sX) {
     constexpr int n = M + 2;
+    if (p->integer_transforms) {
+        const int total = (p->T_pad / 16) * (p->Cin / 32), per_xcd = (total + 7) / 8;
+        const unsigned x_bytes = (unsigned)((size_t)p->N * p->H * p->W * p->Cin * 4);
+        hipLaunchKernelGGL((k_input_transform_int<M>), dim3((unsigned)per_xcd * 8u), dim3(256), 0, s, p->xi, x, Xq,
+                           sX, p->H, p->W, p->Cin, p->TH, p->TW, p->T, p->T_pad, ilog2(p->g / 32),
+                           p->kstep == 32 ? 5 : 6, x_bytes, total, per_xcd);
+        return hipGetLastError();
+    }
     const int tr = p->k1_rows;   // n, n/2, 2 or 1
     if (tr == n) return launch_input_rows<M, n>(p, s, x, Xq, sX);
     if (tr == 1) return launch_input_rows<M, 1>(p, s, x, Xq, sX);

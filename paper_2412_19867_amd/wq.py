@@ -21,7 +21,7 @@ STATUS_NAMES = {0: "WQ_OK", 1: "WQ_ERR_INVALID_ARG", 2: "WQ_ERR_UNSUPPORTED",
                 6: "WQ_ERR_DEVICE"}
 
 EXPORTS = ["wq_standard_transforms", "wq_scaled_transforms", "wq_plan_create", "wq_plan_destroy",
-           "wq_plan_layout", "wq_plan_tune", "wq_conv_forward_debug_slab", "wq_direct_plan_tune",
+           "wq_plan_layout", "wq_plan_tune", "wq_plan_set_integer_transforms", "wq_conv_forward_debug_slab", "wq_direct_plan_tune",
            "wq_contract_output_part", "wq_microbench_dequant", "wq_conv_forward_static",
            "wq_weight_prepare", "wq_input_transform", "wq_contract_output", "wq_contract",
            "wq_output_transform", "wq_conv_forward",
@@ -80,6 +80,7 @@ def lib() -> ctypes.CDLL:
         L.wq_scaled_transforms.argtypes = [ip, vp, vp, vp, vp, vp]
         L.wq_plan_create.argtypes = [ctypes.POINTER(vp), ip, ip, ip, ip, ip, ip, ip, vp, vp, vp]
         L.wq_plan_tune.argtypes = [vp, ip, ip]
+        L.wq_plan_set_integer_transforms.argtypes = [vp, ip]
         L.wq_conv_forward_debug_slab.argtypes = [vp, vp, vp, vp, sz, vp, sz, vp, vp, sz, ip, ip, ip, ip]
         L.wq_direct_plan_tune.argtypes = [vp, ip]
         L.wq_plan_destroy.argtypes = [vp]
@@ -193,6 +194,13 @@ class Plan:
         """Override the plan's kernel choices (wq_plan_tune); k2_variant by number or name."""
         v = K2_VARIANTS[k2_variant] if isinstance(k2_variant, str) else int(k2_variant)
         _check(lib().wq_plan_tune(self._h, int(k1_rows), v), "wq_plan_tune")
+        _check(lib().wq_plan_layout(self._h, ctypes.byref(self.layout)), "wq_plan_layout")
+        return self
+
+    def set_integer_transforms(self, mode: int = 1):
+        """Fully-integer input and output transforms (wq_plan_set_integer_transforms): 0 off,
+        1 one scale per transform matrix, 2 one scale per matrix row."""
+        _check(lib().wq_plan_set_integer_transforms(self._h, int(mode)), "wq_plan_set_integer_transforms")
         _check(lib().wq_plan_layout(self._h, ctypes.byref(self.layout)), "wq_plan_layout")
         return self
 

@@ -261,3 +261,26 @@ def test_weight_bits_of_direct_and_linear_plans(wq):
     assert p4.layout.ws_bytes == p8.layout.ws_bytes
     c4 = wq.DirectPlan(1, 5, 5, 64, 16, 32, weight_bits=4)
     assert c4.layout.taps == 9 and c4.layout.blob_sW_off == (9 * 32 * 64 // 2 + 255) // 256 * 256
+
+
+def test_integer_transform_mode_is_host_state_only(wq):
+    """wq_plan_set_integer_transforms: argument checks, the forced two-kernel variant and full tap
+    rows, refusal of variants that never hold a Winograd-domain tile, and mode 0 undoing it."""
+    assert wq.lib().wq_plan_set_integer_transforms(None, 1) == 1
+    p = wq.Plan(2, 64, 64, 640, 320, 4, 64)
+    before = (p.layout.k2_variant, p.layout.k1_rows, p.layout.ws_bytes, p.layout.blob_bytes)
+    assert wq.lib().wq_plan_set_integer_transforms(p._h, 3) == 1
+    for mode in (1, 2):
+        p.set_integer_transforms(mode)
+        assert p.layout.k2_kernels == 2 and p.layout.k1_rows == 6
+        assert p.k2_variant_name.startswith(("gemm", "lds_tap"))
+        for name in ("fused_32x16", "lds_row_64x64", "lds_full_64x64"):
+            with pytest.raises(wq.WqError) as e:
+                p.tune(0, name)
+            assert e.value.status == 2
+        with pytest.raises(wq.WqError):
+            p.tune(3, "auto")                 # the patch scale needs all tap rows in one workgroup
+        p.tune(0, "gemm_64x64")
+        assert (p.layout.ws_bytes, p.layout.blob_bytes) == before[2:]
+    p.set_integer_transforms(0)
+    assert (p.layout.k2_variant, p.layout.k1_rows, p.layout.ws_bytes, p.layout.blob_bytes) == before

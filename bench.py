@@ -485,7 +485,7 @@ def main():
             integer = dict(value=round(direct_ops / i_sec / 1e12, 2), unit="TOPS", ms_per_step=round(i_sec * 1e3, 4),
                            launch=min(i_t, key=i_t.get), scales="one per transform matrix",
                            k2_variants=sorted({it["plan"].k2_variant_name for it in i_items}),
-                           fp32_transforms_over_integer=round(i_sec / sec, 3))
+                           integer_over_fp32_time=round(i_sec / sec, 3))
             del i_items
             torch.cuda.empty_cache()
 

@@ -23,19 +23,16 @@
 // Workgroups are numbered so that the eight XCDs (which receive consecutive
 // workgroup ids round-robin and have private L2s) each own a slice of the
 // larger operand: with xcd_mode 0 an XCD owns every 8th block of output
-// channels (weights stay in its L2), with xcd_mode 1 every 8th block of tiles.
+// channels (weights stay in its L2), with xcd_mode 1 every 8th block of tiles,
+// with xcd_mode 2 every 4th block of tiles and one half of the channels.
 #pragma once
-
-#include <stdlib.h>
 
 #include "wq_device.h"
 #include "wq_internal.h"
 
 namespace {   // every including file instantiates its own tile size; nothing here is exported
 
-#ifndef WQ_D_BASE
-#define WQ_D_BASE 4
-#endif
+constexpr int kPrefetchBase = 4;         // K-steps in flight of the 16x16 configurations
 constexpr int RS_STRIDE = 20;           // floats per tile row of the LDS exchange (16 + pad)
 
 struct Args {
@@ -78,9 +75,13 @@ __global__ __launch_bounds__(64 * (M + 2) * KS) void k_contract_output(const Arg
         if (a.xcd_mode == 0) {
             ob = (s / a.nTB) * 8 + xcd;
             tb = s % a.nTB;
-        } else {
+        } else if (a.xcd_mode == 1) {
             tb = (s / a.nOB) * 8 + xcd;
             ob = s % a.nOB;
+        } else {   // 4 parts of the tiles x 2 halves of the channels
+            const int hob = (a.nOB + 1) >> 1;
+            tb = (s / hob) * 4 + (xcd >> 1);
+            ob = (xcd & 1) * hob + s % hob;
         }
         if (tb >= a.nTB || ob >= a.nOB) return;
     }
@@ -366,8 +367,14 @@ hipError_t launch_cfg(const Args &a, hipStream_t s) {
     // the XCDs partition the blocks of the larger operand
     const long wbytes = (long)a.Cout_pad * a.Cin, xbytes = (long)a.T_pad * a.Cin;
     b.xcd_mode = wbytes >= xbytes ? 0 : 1;
+    // tiles split over the XCDs, but all taps' weights would fill an XCD's 4 MB L2 on their own:
+    // split the channels in two as well, so that half of the weights stays resident next to the
+    // streaming activations
+    const long wall = wbytes * (M + 2) * (M + 2);
+    if (b.xcd_mode == 1 && wall > (5L << 19) && wall <= (8L << 20) && b.nOB >= 2) b.xcd_mode = 2;
     const int split = b.xcd_mode == 0 ? b.nOB : b.nTB, other = b.xcd_mode == 0 ? b.nTB : b.nOB;
-    const unsigned grid = (unsigned)(((split + 7) / 8) * 8 * other);
+    const unsigned grid = b.xcd_mode == 2 ? (unsigned)(((b.nTB + 3) / 4) * ((b.nOB + 1) / 2) * 8)
+                                          : (unsigned)(((split + 7) / 8) * 8 * other);
     if (a.dump.P)
         hipLaunchKernelGGL((k_contract_output<M, K64, CPG1, WIDE, ATSP, true, NT, NO, KS, D>), dim3(grid),
                            dim3(64 * (M + 2) * KS), 0, s, b);
@@ -380,16 +387,16 @@ hipError_t launch_cfg(const Args &a, hipStream_t s) {
 // fp64 chunk totals only where a wave reduces more than 8 groups per tap
 template <int M, bool K64, bool CPG1, bool ATSP>
 hipError_t launch_base(const Args &a, hipStream_t s, bool wide) {
-    return wide ? launch_cfg<M, K64, CPG1, true, ATSP, 1, 1, 1, WQ_D_BASE>(a, s)
-                : launch_cfg<M, K64, CPG1, false, ATSP, 1, 1, 1, WQ_D_BASE>(a, s);
+    return wide ? launch_cfg<M, K64, CPG1, true, ATSP, 1, 1, 1, kPrefetchBase>(a, s)
+                : launch_cfg<M, K64, CPG1, false, ATSP, 1, 1, 1, kPrefetchBase>(a, s);
 }
 
 // the register-tile variants: one K-step per group, paired form of A^T
 template <int M, bool K64>
 hipError_t launch_fast(const Args &a, hipStream_t s, int variant, bool wide) {
     if (variant == WQ_K2_FUSED_KSPLIT)
-        return wide ? launch_cfg<M, K64, true, true, true, 1, 1, 2, WQ_D_BASE>(a, s)
-                    : launch_cfg<M, K64, true, false, true, 1, 1, 2, WQ_D_BASE>(a, s);
+        return wide ? launch_cfg<M, K64, true, true, true, 1, 1, 2, kPrefetchBase>(a, s)
+                    : launch_cfg<M, K64, true, false, true, 1, 1, 2, kPrefetchBase>(a, s);
     if (variant == WQ_K2_FUSED_32x16)
         return wide ? launch_cfg<M, K64, true, true, true, 2, 1, 1, 3>(a, s)
                     : launch_cfg<M, K64, true, false, true, 2, 1, 1, 3>(a, s);

@@ -88,7 +88,10 @@ hipError_t wq_launch_contract_lds(const wq_plan *p, hipStream_t s, const int8_t 
     a.log2g = 0;
     while ((1 << a.log2g) < p->g) ++a.log2g;
     a.nOBt = a.nTBt = a.total = a.per_xcd = a.tb_fastest = 0;
-    a.plain_stores = (long long)p->n * p->n * p->T_pad * p->Cout_pad * 4 > (128LL << 20);
+    {   // bytes of the intermediate: n*n products per element for the tap form, n*m row sums for the row form
+        const long long per_elem = wq_is_lds_tap_variant(p->k2_variant) ? p->n * p->n : p->n * p->m;
+        a.plain_stores = per_elem * p->T_pad * p->Cout_pad * 4 >= (20LL << 20);
+    }
     if (p->m != 4 && p->m != 6) return hipErrorInvalidValue;   // the plan never picks these variants for F(2,3)
     hipError_t e = hipSuccess;
     if (parts & 1) {

@@ -29,7 +29,7 @@
 // MFMAs run under the dequantization costs 16 registers and measured slower than what the extra
 // resident workgroup does with them (MFMA and vector-ALU time add up on a SIMD either way).
 //
-// Two forms:
+// Three forms:
 //   FULL  a workgroup walks all n*n taps and stores y (NHWC, ragged edge masked): one kernel,
 //         nothing but y leaves the chip.  Needs (tiles x channels)/(workgroup tile) workgroups
 //         to fill the GPU, i.e. many tiles.

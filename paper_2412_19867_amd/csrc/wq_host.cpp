@@ -185,8 +185,8 @@ int default_k2_variant(const wq_plan *p) {
     // and each of them walks a reduction long enough to pay for the second kernel.
     if (variant_applicable(p, WQ_K2_LDS_ROW_64x64) && p->g == p->kstep && p->groups >= 8) {
         const long wgs = (long)((p->T_pad + 63) / 64) * ((p->Cout_pad + 63) / 64) * (p->m + 2);
-        // (... or many times over on layers that are large in tiles AND channels, where the products the
-        // two-kernel forms write would be several hundred MB)
+        // also layers large in tiles AND output channels, where the Winograd-domain product the
+        // two-kernel forms write would reach hundreds of MB
         if (wgs >= 384 && (wgs <= 768 || (p->T_pad >= 1024 && p->Cout_pad >= 512))) return WQ_K2_LDS_ROW_64x64;
     }
     // With few tiles the Winograd-domain result is small next to the operands, and a tiled GEMM

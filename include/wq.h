@@ -142,6 +142,7 @@ typedef enum {
     WQ_K2_GEMM_128x128 = 12,
     WQ_K2_LDS_FULL_64x64 = 20,
     WQ_K2_LDS_FULL_32x64 = 21,
+    WQ_K2_LDS_FULL_32x32 = 22,
     WQ_K2_LDS_ROW_64x64 = 30,
     WQ_K2_LDS_ROW_32x64 = 31,
     WQ_K2_LDS_TAP_64x64 = 40,

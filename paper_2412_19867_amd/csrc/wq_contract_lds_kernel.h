@@ -534,6 +534,9 @@ void launch_variant(const LArgs &a, hipStream_t s, int variant) {
         case WQ_K2_LDS_FULL_32x64:
             launch_tile<M, K64, CPG1, WIDE, true, DUMP, 4, 2 / FBM, 1, FBM, 8>(a, s);
             break;
+        case WQ_K2_LDS_FULL_32x32:   // one block per wave: four workgroups per CU, their waves interleave on a SIMD
+            launch_tile<M, K64, CPG1, WIDE, true, DUMP, 2, 2, 1, 1, 8>(a, s);
+            break;
         case WQ_K2_LDS_ROW_64x64:
             launch_tile<M, K64, CPG1, WIDE, false, DUMP, 2, 2, 2, 2, 6>(a, s);   // 3 workgroups' rings per CU
             break;

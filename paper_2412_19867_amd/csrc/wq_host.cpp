@@ -167,6 +167,7 @@ bool variant_applicable(const wq_plan *p, int v) {
         case WQ_K2_GEMM_128x128: return p->g >= 128 && p->groups <= 8;
         case WQ_K2_LDS_FULL_64x64: return p->m == 4;   // 16 waves of F(6,3) state do not fit the registers
         case WQ_K2_LDS_FULL_32x64:
+        case WQ_K2_LDS_FULL_32x32:
         case WQ_K2_LDS_ROW_64x64:
         case WQ_K2_LDS_ROW_32x64:
         case WQ_K2_LDS_TAP_64x64: return p->m != 2;    // instantiated for F(4,3) and F(6,3)
@@ -205,6 +206,14 @@ int default_k2_variant(const wq_plan *p) {
         if (p->T_pad >= 128 && p->T_pad <= 512 && p->g < 128 && variant_applicable(p, WQ_K2_LDS_TAP_64x64))
             return WQ_K2_LDS_TAP_64x64;
         return WQ_K2_GEMM_64x64;
+    }
+    // Many tiles and a short reduction (the 128 x 128, 320-channel layer): one 16x16 block per wave with
+    // the operands shared through LDS, four workgroups of 32 tiles x 32 channels per CU.  A workgroup
+    // walks all n*n taps in sequence, so the reduction must be short and the workgroups must fill
+    // the GPU at least twice over; the fused kernel below has the same traffic but fewer, fatter waves.
+    if (p->m == 4 && p->g == p->kstep && variant_applicable(p, WQ_K2_LDS_FULL_32x32)) {
+        const long wgs = (long)((p->T_pad + 31) / 32) * ((p->Cout_pad + 31) / 32);
+        if (wgs >= 512 && p->groups <= 6) return WQ_K2_LDS_FULL_32x32;
     }
     if (!variant_applicable(p, WQ_K2_FUSED_32x16)) return WQ_K2_FUSED_16x16;
     // few tile blocks -> split K over more waves; many blocks -> taller or bigger register tiles
@@ -364,7 +373,7 @@ wq_status_t wq_plan_tune(wq_plan_t *plan, int k1_rows, int k2_variant) {
         case WQ_K2_AUTO:
         case WQ_K2_FUSED_16x16: case WQ_K2_FUSED_KSPLIT: case WQ_K2_FUSED_32x16: case WQ_K2_FUSED_32x32:
         case WQ_K2_GEMM_64x64: case WQ_K2_GEMM_32x128: case WQ_K2_GEMM_128x128:
-        case WQ_K2_LDS_FULL_64x64: case WQ_K2_LDS_FULL_32x64:
+        case WQ_K2_LDS_FULL_64x64: case WQ_K2_LDS_FULL_32x64: case WQ_K2_LDS_FULL_32x32:
         case WQ_K2_LDS_ROW_64x64: case WQ_K2_LDS_ROW_32x64: case WQ_K2_LDS_TAP_64x64: case WQ_K2_LDS_TAP_128x128: break;
         default: return WQ_ERR_INVALID_ARG;
     }

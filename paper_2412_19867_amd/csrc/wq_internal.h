@@ -96,7 +96,7 @@ __device__ __forceinline__ void wq_apply_at(const wq_xf &xf, const float (&v)[M 
 
 inline bool wq_is_gemm_variant(int v) { return v >= WQ_K2_GEMM_64x64 && v <= WQ_K2_GEMM_128x128; }
 inline bool wq_is_fused_variant(int v) { return v >= WQ_K2_FUSED_16x16 && v <= WQ_K2_FUSED_32x32; }
-inline bool wq_is_lds_full_variant(int v) { return v >= WQ_K2_LDS_FULL_64x64 && v <= WQ_K2_LDS_FULL_32x64; }
+inline bool wq_is_lds_full_variant(int v) { return v >= WQ_K2_LDS_FULL_64x64 && v <= WQ_K2_LDS_FULL_32x32; }
 inline bool wq_is_lds_row_variant(int v) { return v >= WQ_K2_LDS_ROW_64x64 && v <= WQ_K2_LDS_ROW_32x64; }
 inline bool wq_is_lds_tap_variant(int v) { return v == WQ_K2_LDS_TAP_64x64 || v == WQ_K2_LDS_TAP_128x128; }
 inline bool wq_is_lds_variant(int v) {

@@ -53,7 +53,7 @@ class DirectLayout(ctypes.Structure):
 # wq_k2_variant_t (include/wq.h): the kernel instance of stages 2+3
 K2_VARIANTS = {"auto": -1, "fused_16x16": 0, "fused_ksplit": 1, "fused_32x16": 2, "fused_32x32": 3,
                "gemm_64x64": 10, "gemm_32x128": 11, "gemm_128x128": 12,
-               "lds_full_64x64": 20, "lds_full_32x64": 21, "lds_row_64x64": 30, "lds_row_32x64": 31,
+               "lds_full_64x64": 20, "lds_full_32x64": 21, "lds_full_32x32": 22, "lds_row_64x64": 30, "lds_row_32x64": 31,
                "lds_tap_64x64": 40, "lds_tap_128x128": 41}
 K2_VARIANT_NAMES = {v: k for k, v in K2_VARIANTS.items()}
 

@@ -318,7 +318,7 @@ VARIANT_SHAPES = [
     (207, 1, 24, 24, 768, 70, 6, 32, True),     # F(6,3), 24 groups, odd channel count
 ]
 ALL_VARIANTS = ["fused_16x16", "fused_ksplit", "fused_32x16", "fused_32x32", "gemm_64x64", "gemm_32x128",
-                "gemm_128x128", "lds_full_64x64", "lds_full_32x64", "lds_row_64x64", "lds_row_32x64",
+                "gemm_128x128", "lds_full_64x64", "lds_full_32x64", "lds_full_32x32", "lds_row_64x64", "lds_row_32x64",
                 "lds_tap_64x64", "lds_tap_128x128"]
 
 

@@ -449,8 +449,11 @@ __global__ __launch_bounds__(64 * NWO * NWT, 2) void k_wino_lds(const LArgs a) {
                         const float4 Yv = Y[aa][b][no][nt];
                         float *dst = base + ((size_t)aa * a.W + b) * a.Cout + o;
                         const v4f out = {Yv.x + bv4.x, Yv.y + bv4.y, Yv.z + bv4.z, Yv.w + bv4.w};
-                        if (vec) {   // streaming store: y is not read again by this layer
-                            store_y(out, reinterpret_cast<v4f *>(dst));
+                        if (vec) {
+                            // a plain store: this form runs on layers with many tiles, whose output the
+                            // next layer's input kernel finds in the caches (measured on a chained
+                            // stack: -0.9 % of the whole step against the streaming store)
+                            *reinterpret_cast<v4f *>(dst) = out;
                         } else {
 #pragma unroll
                             for (int r = 0; r < 4; ++r)

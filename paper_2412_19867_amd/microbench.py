@@ -7,6 +7,12 @@ peak that rate corresponds to.  The dequantization is 12 vector instructions per
 group whatever the group size; the MFMA work per group grows with it.
 
     python -m paper_2412_19867_amd.microbench            # table on stdout
+
+`--cache-probe` instead measures a property of the memory system that a chain of layers runs
+into: how fast a kernel reads data it has never touched, depending on whether the last-level
+(Infinity) cache holds dirty lines another kernel has just written, or clean ones.
+
+    python -m paper_2412_19867_amd.microbench --cache-probe
 """
 from __future__ import annotations
 
@@ -46,7 +52,59 @@ def run(iters: int = 20000):
     return rows
 
 
+def cache_probe():
+    """A read-only stream (a library reduction over int64 words) over `mb` MB of cold data, timed with
+    events, after (a) a 1 GiB buffer has just been filled (its lines sit dirty in the caches and are
+    written back as the reader's lines displace them), (b) the same buffer has just been read twice
+    (clean lines), (c) filled, then 300 MB of it read; and over the same data a second time."""
+    import statistics
+    import torch
+    big = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+    big64 = big.view(torch.int64)
+    out = torch.zeros(2, dtype=torch.int64, device="cuda")
+
+    def read(t, slot):
+        torch.sum(t, dim=0, keepdim=True, out=out[slot:slot + 1])
+
+    def med_us(prepare, data):
+        ts = []
+        for rep in range(12):
+            prepare(rep)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            read(data, 1)
+            e1.record()
+            torch.cuda.synchronize()
+            if rep >= 2:
+                ts.append(e0.elapsed_time(e1) * 1e3)
+        return statistics.median(ts)
+
+    def dirty(rep):
+        big.fill_(rep & 1)
+
+    def clean(rep):
+        big.fill_(rep & 1)
+        read(big64, 0)
+        read(big64, 0)
+
+    def dirty_then_read(rep):
+        big.fill_(rep & 1)
+        read(big64[: (300 << 20) // 8], 0)
+
+    for mb in (60, 240, 480):
+        data = torch.ones(mb << 20, dtype=torch.uint8, device="cuda").view(torch.int64)
+        for name, prep in (("1 GiB written just before (dirty lines)", dirty),
+                           ("1 GiB read just before (clean lines)", clean),
+                           ("1 GiB written, then 300 MB of it read", dirty_then_read),
+                           ("the same data read just before", lambda rep: read(data, 1))):
+            t = med_us(prep, data)
+            print(f"{mb:4d} MB read after [{name:40s}]: {t:7.1f} us = {(mb << 20) / t / 1e6:5.2f} TB/s", flush=True)
+
+
 def main():
+    if "--cache-probe" in sys.argv:
+        cache_probe()
+        return
     rows = run()
     if "--json" in sys.argv:
         print(json.dumps(rows))

@@ -165,10 +165,17 @@ def main():
             for r in range(lay.repeat):
                 # conv r of a stack reads conv r-1's output (Cin == Cout) and has its own weight blob
                 it = dict(lay=lay, plan=plan, x=x, w=w, b=b, blob=plan.alloc_blob(),
-                          ws=plan.alloc_workspace(), y=plan.alloc_output(), data=d, first=(r == 0))
+                          ws=None, y=plan.alloc_output(), data=d, first=(r == 0))
                 plan.weight_prepare(w, b, it["blob"])
                 items.append(it)
                 x = it["y"]
+        # One workspace for all convolutions of the step, as large as the largest needs: they run one
+        # after the other on one stream and a forward pass writes every workspace byte before it reads
+        # it.  (Per-convolution workspaces measure 0.8 % slower: the dead intermediates of one layer
+        # are overwritten in the caches by the next instead of being written back to memory.)
+        ws_all = torch.empty(max(it["plan"].layout.ws_bytes for it in items), dtype=torch.uint8, device="cuda")
+        for it in items:
+            it["ws"] = ws_all[:it["plan"].layout.ws_bytes]
         torch.cuda.synchronize()
         return items
 
@@ -245,8 +252,8 @@ def main():
 
     g_off = capture(lambda: step(True))
     sec_off, _ = timed(g_off.replay, max(5, args.steps // 4), 2, repeats=5)
-    footprint = sum(it["x"].numel() * 4 * it["first"] + it["blob"].numel() + it["ws"].numel()
-                    + it["y"].numel() * 4 for it in items)
+    footprint = sum(it["x"].numel() * 4 * it["first"] + it["blob"].numel()
+                    + it["y"].numel() * 4 for it in items) + max(it["ws"].numel() for it in items)
 
     # ---- per-kernel durations, measured inside the real sequence: an instrumented step launches
     # every kernel of every convolution in order on the replay stream with a HIP event between

@@ -261,7 +261,7 @@ def main():
     # while the host enqueues the whole step, so that an interval holds its kernel (plus what
     # an event costs, measured on empty intervals of the same pass and subtracted) and no host
     # launch gap; it also leaves the caches as cold as they are when
-    # the step is replayed back to back (a step touches 1.5 GB on the headline workload).  Median
+    # the step is replayed back to back (a step moves 1.9 GB on the headline workload).  Median
     # of REPS instrumented steps.  The offline weight stage is timed on its own (back to back).
     REPS = 15
     spacer = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")

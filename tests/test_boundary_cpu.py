@@ -111,6 +111,31 @@ def test_plan_tune_is_validated_on_the_host(wq):
         lin.tune(3)
 
 
+def test_the_plans_own_variant_choice_always_applies(wq):
+    """Over a grid of shapes, tile sizes and group sizes (both transform modes): the variant a plan
+    picks for itself is a listed one, and forcing exactly that variant is accepted - the selection
+    rules never name a kernel instance the shape, group size or matrices rule out."""
+    import itertools
+    codes = set(wq.K2_VARIANTS.values())
+    picked = set()
+    shapes = [(1, 8, 8), (1, 20, 36), (2, 64, 64), (2, 128, 128), (8, 96, 96), (32, 14, 14), (32, 56, 56), (4, 33, 17)]
+    chans = [(32, 32), (64, 48), (128, 256), (320, 320), (640, 640), (1280, 1280), (960, 320), (256, 1024), (1536, 64)]
+    for (N, H, W), (ci, co), m, g in itertools.product(shapes, chans, (2, 4, 6), (32, 64, 128, 256)):
+        if ci % g:
+            continue
+        p = wq.Plan(N, H, W, ci, co, m, g)
+        for mode in (0, 1):
+            if mode:
+                p.set_integer_transforms(mode)
+            v = p.layout.k2_variant
+            assert v in codes, (N, H, W, ci, co, m, g, mode, v)
+            p.tune(0, v)                      # raises WqError if the plan's own choice does not apply
+            assert p.layout.k2_variant == v
+            picked.add(p.k2_variant_name)
+    # the grid reaches every family the rules can pick
+    assert {n.rsplit("_", 1)[0] for n in picked} >= {"fused", "gemm", "lds_full", "lds_row", "lds_tap"}
+
+
 def test_layout_numbers(wq):
     p = wq.Plan(2, 7, 9, 64, 40, 4, 32)
     L = p.layout

@@ -123,7 +123,8 @@ wq_status_t wq_plan_layout(const wq_plan_t *plan, wq_layout_t *out);
  *             the workspace (tiles x channels per workgroup), then an output-transform kernel;
  *   LDS_FULL_* one kernel, every wave of a workgroup on the same tap, operand tiles staged
  *             once per K-step in LDS and shared, the output transform accumulated tap row
- *             by tap row in registers (tiles x channels per workgroup);
+ *             by tap row in registers (tiles x channels per workgroup; 32x32 = one 16x16
+ *             block per wave and four workgroups per CU, for many tiles and short reductions);
  *   LDS_ROW_*  one workgroup per (tile block, channel block, tap row): the same staged
  *             contraction over the n taps of a row folded into row sums of Y A, which go
  *             to the workspace; a small second kernel applies A^T and the bias;
